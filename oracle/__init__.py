@@ -1,0 +1,188 @@
+"""ctypes front end of the plain-C CPU oracle (``monta_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the benchmark's
+``cpu_baseline`` leg use it; the product package never imports it, and it never
+imports the product package.  The C file is compiled with plain ``gcc`` (no HIP).
+
+All functions take and return numpy arrays.  bf16 activations travel as
+``uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "monta_oracle.c")
+_LIB = os.path.join(_HERE, "libmonta_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  -O1 and no fast-math: keep it plain and IEEE."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fno-fast-math",
+               "-ffp-contract=off", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.monta_oracle_capacity.restype = ctypes.c_int64
+        _lib.monta_oracle_capacity.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double]
+    return _lib
+
+
+def _p(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"oracle {what}: error {rc}")
+
+
+def capacity(T: int, E: int, k: int, cf: float) -> int:
+    return int(_load().monta_oracle_capacity(T, E, k, float(cf)))
+
+
+def route(logits: np.ndarray, k: int, renorm: int = 1):
+    """logits float32 [T,E] -> (topk_idx int32 [T,k], gates float32 [T,k])."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    if not np.isfinite(logits).all():
+        raise ValueError("oracle route: logits must be finite")
+    T, E = logits.shape
+    idx = np.empty((T, k), np.int32)
+    gates = np.empty((T, k), np.float32)
+    rc = _load().monta_oracle_route(ctypes.c_int64(T), E, k, int(renorm), _p(logits), _p(idx), _p(gates))
+    _check(rc, "route")
+    return idx, gates
+
+
+@dataclass
+class Plan:
+    C: int
+    R: int
+    alive: int
+    counts: np.ndarray      # [E]
+    kept: np.ndarray        # [E]
+    offsets: np.ndarray     # [E+1]
+    pos_final: np.ndarray   # [T,k]
+    n: np.ndarray           # [U,E]
+    stage_off: np.ndarray   # [U,E]
+    unit_base: np.ndarray   # [U,E]
+    pos_stage: np.ndarray   # [T,k]
+    send_rows: np.ndarray   # [U,ep]
+
+
+def plan(topk_idx: np.ndarray, E: int, ep: int, tp: int, S: int, cf: float) -> Plan:
+    topk_idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
+    T, k = topk_idx.shape
+    U = S * tp
+    counts = np.empty(E, np.int32)
+    kept = np.empty(E, np.int32)
+    offsets = np.empty(E + 1, np.int32)
+    pos_final = np.empty((T, k), np.int32)
+    n = np.empty((U, E), np.int32)
+    stage_off = np.empty((U, E), np.int32)
+    unit_base = np.empty((U, E), np.int32)
+    pos_stage = np.empty((T, k), np.int32)
+    send_rows = np.empty((U, ep), np.int32)
+    alive = ctypes.c_int64(0)
+    rc = _load().monta_oracle_plan(ctypes.c_int64(T), E, k, ep, tp, S, ctypes.c_double(cf), _p(topk_idx),
+                                   _p(counts), _p(kept), _p(offsets), _p(pos_final), _p(n), _p(stage_off),
+                                   _p(unit_base), _p(pos_stage), _p(send_rows), ctypes.byref(alive))
+    _check(rc, "plan")
+    return Plan(capacity(T, E, k, cf), int(offsets[E]), int(alive.value), counts, kept, offsets, pos_final,
+                n, stage_off, unit_base, pos_stage, send_rows)
+
+
+def pack(x: np.ndarray, pl: Plan, tp: int, S: int, stage: np.ndarray | None = None, slice_: int = -1,
+         fill: int = 0) -> np.ndarray:
+    """x [T,H] (float32 or uint16) -> STAGE [R,H].  Rows are bit copies."""
+    x = np.ascontiguousarray(x)
+    T, H = x.shape
+    k = pl.pos_stage.shape[1]
+    if stage is None:
+        stage = np.full((pl.R, H), fill, dtype=x.dtype)
+    rc = _load().monta_oracle_pack(ctypes.c_int64(T), k, tp, S, ctypes.c_int64(H * x.itemsize), _p(x),
+                                   _p(pl.pos_stage), _p(stage), slice_)
+    _check(rc, "pack")
+    return stage
+
+
+def regather(stage: np.ndarray, pl: Plan, tp: int, S: int, final: np.ndarray | None = None,
+             slice_: int = -1, fill: int = 0) -> np.ndarray:
+    stage = np.ascontiguousarray(stage)
+    H = stage.shape[1]
+    E = pl.counts.shape[0]
+    if final is None:
+        final = np.full((pl.R, H), fill, dtype=stage.dtype)
+    rc = _load().monta_oracle_regather(tp, S, E, ctypes.c_int64(H * stage.itemsize), _p(pl.n), _p(pl.stage_off),
+                                       _p(pl.unit_base), _p(stage), _p(final), slice_)
+    _check(rc, "regather")
+    return final
+
+
+def combine(y: np.ndarray, gates: np.ndarray, pos_final: np.ndarray) -> np.ndarray:
+    """y [R,H] float32 or uint16(bf16) -> out [T,H] of the same type."""
+    y = np.ascontiguousarray(y)
+    gates = np.ascontiguousarray(gates, dtype=np.float32)
+    pos_final = np.ascontiguousarray(pos_final, dtype=np.int32)
+    T, k = pos_final.shape
+    H = y.shape[1]
+    if y.dtype == np.float32:
+        dtype = 0
+    elif y.dtype == np.uint16:
+        dtype = 1
+    else:
+        raise ValueError("oracle combine: y must be float32 or uint16 (bf16 bits)")
+    if pos_final.max(initial=-1) >= y.shape[0]:
+        raise ValueError("oracle combine: position outside y")
+    out = np.empty((T, H), y.dtype)
+    rc = _load().monta_oracle_combine(ctypes.c_int64(T), H, k, dtype, _p(y), _p(gates), _p(pos_final), _p(out))
+    _check(rc, "combine")
+    return out
+
+
+def volume(pl: Plan, tp: int, S: int, row_bytes: int):
+    """-> (unit_bytes [U], dest_bytes [U,ep], slice_gather_bytes [S]) as int64."""
+    U, E = pl.n.shape
+    ep = pl.send_rows.shape[1]
+    unit_bytes = np.empty(U, np.int64)
+    dest_bytes = np.empty((U, ep), np.int64)
+    slice_bytes = np.empty(S, np.int64)
+    rc = _load().monta_oracle_volume(tp, S, E, ep, ctypes.c_int64(row_bytes), _p(pl.n), _p(pl.send_rows),
+                                     _p(unit_bytes), _p(dest_bytes), _p(slice_bytes))
+    _check(rc, "volume")
+    return unit_bytes, dest_bytes, slice_bytes
+
+
+@dataclass
+class Result:
+    topk_idx: np.ndarray
+    gates: np.ndarray
+    plan: Plan
+    stage: np.ndarray
+    final: np.ndarray
+    out: np.ndarray
+
+
+def forward(logits, x, *, k, ep, tp, S, cf, renorm=1) -> Result:
+    """The whole path with identity experts (expert output = FINAL)."""
+    E = logits.shape[1]
+    idx, gates = route(logits, k, renorm)
+    pl = plan(idx, E, ep, tp, S, cf)
+    stage = pack(x, pl, tp, S)
+    final = regather(stage, pl, tp, S)
+    out = combine(final, gates, pl.pos_final)
+    return Result(idx, gates, pl, stage, final, out)
