@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE dispatch + combine hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input that is
+already resident in HBM: monta_route (top-k, gates, counting-sort plan) ->
+monta_dispatch_regather (S-slice pack / regather pipeline) -> monta_combine
+(identity experts: the expert output is FINAL).
+
+Prints ONE JSON line.  `value` is tokens/s of the whole job; `roofline` is the
+dominant kernel's algorithmic bytes per launch over its average launch duration,
+measured here with HIP events on the launching stream; `cpu_baseline` is the CPU
+oracle timed on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(w, tabs):
+    """Bytes the method itself must move (per kernel class and per pipeline launch)."""
+    row = w.row_bytes
+    T, k, E, S, tp = w.tokens, w.top_k, w.experts, w.slices, w.tp
+    pos = tabs["pos_final"]
+    alive_tok = (pos >= 0).any(axis=1)
+    per_slice_tok = T // S
+    alive_s = alive_tok.reshape(S, per_slice_tok).sum(axis=1).astype(np.int64)
+    rows_s = tabs["n"].reshape(S, tp * E).sum(axis=1).astype(np.int64)
+    R = int(rows_s.sum())
+    alive = int(alive_s.sum())
+    idx_bytes = T * E * 4 + T * k * 8 + 6 * T * k * 4
+    out = {
+        "row": row, "R": R, "alive": alive,
+        "route": T * E * 4 + T * k * 8, "plan": 6 * T * k * 4,
+        "pack": (alive + R) * row + T * k * 4,
+        "regather": 2 * R * row + R * 4,
+        "combine": (R + T) * row + T * k * 8,
+        "pack_s": [(int(alive_s[j]) + int(rows_s[j])) * row for j in range(S)],
+        "regather_s": [2 * int(rows_s[j]) * row for j in range(S)],
+    }
+    out["total"] = (alive + T + 4 * R) * row + idx_bytes
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", default="mixtral", help="tiny | mixtral | 2x70b | longctx | skewed")
+    ap.add_argument("--slices", type=int, default=0, help="override the workload's slice count")
+    ap.add_argument("--mode", type=int, default=-1, help="pipeline realisation 0/1/2 (default: library default)")
+    ap.add_argument("--graph", type=int, default=1, help="replay the step from a captured HIP graph (1) or launch eagerly (0)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build covers one GPU's share of the path; nothing crosses GPUs, so only --gpus 1 is "
+              "supported (virtual EP/TP ranks are buffer partitions on one MI355X).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    import paper_2411_00662_amd as m
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    m.binding.lib()     # no fallback: fails here if the HIP library is not built
+
+    w = workloads.CONFIGS[args.config]
+    if args.slices:
+        w = w.with_(slices=args.slices)
+    if args.mode >= 0:
+        m.monta_set_pipeline_mode(args.mode)
+    mode = m.monta_get_pipeline_mode()
+    logits, x = workloads.make_inputs(w)
+    cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm)
+    b = m.alloc_buffers(cfg, logits, x)
+
+    stream = torch.cuda.Stream()          # default priority; the whole step is enqueued on it
+
+    def step():
+        m.monta_route(cfg, b.logits, b.topk_idx, b.gates, b.ws, stream)
+        m.monta_dispatch_regather(cfg, b.x, b.stage, b.final, b.ws, stream)
+        m.monta_combine(cfg, b.final, b.gates, b.out, b.ws, stream)
+
+    torch.cuda.synchronize()
+    use_graph = bool(args.graph)
+    graph = None
+    with torch.cuda.stream(stream):
+        step()                              # first touch, also creates the side stream before any capture
+        stream.synchronize()
+        if use_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                step()
+            run = graph.replay
+        else:
+            run = step
+        for _ in range(args.warmup):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = w.tokens / (ms_per_step * 1e-3)
+
+    tabs = m.read_tables(cfg, b.ws)
+    ab = algorithmic_bytes(w, tabs)
+    eff_gbps = ab["total"] / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel durations: HIP events around every launch, on the launching stream, eager launches
+    roofline = None
+    kernels = {}
+    if not args.no_profile:
+        m.monta_profile_reset()
+        m.monta_profile_enable(True)
+        prof_steps = min(args.steps, 100)
+        with torch.cuda.stream(stream):
+            for _ in range(prof_steps):
+                step()
+            torch.cuda.synchronize()
+        m.monta_profile_enable(False)
+        for kid, name in enumerate(m.KERNEL_NAMES):
+            ms, n = m.monta_profile_read(kid)
+            if n:
+                kernels[name] = {"launches_per_step": n / prof_steps, "avg_us": ms * 1e3 / n,
+                                 "us_per_step": ms * 1e3 / prof_steps}
+        m.monta_profile_reset()
+        S = w.slices
+        per_launch = {"pack": None, "regather": None, "pack_regather": None, "combine": ab["combine"]}
+        if "pack" in kernels:
+            npk = round(kernels["pack"]["launches_per_step"])
+            per_launch["pack"] = (sum(ab["pack_s"]) if mode != 1 else ab["pack_s"][0]) / npk
+        if "regather" in kernels:
+            nrg = round(kernels["regather"]["launches_per_step"])
+            per_launch["regather"] = (sum(ab["regather_s"]) if mode != 1 else ab["regather_s"][S - 1]) / nrg
+        if "pack_regather" in kernels:
+            tot = sum(ab["pack_s"][j] + ab["regather_s"][j - 1] for j in range(1, S))
+            per_launch["pack_regather"] = tot / (S - 1)
+        movers = [kname for kname in ("pack", "regather", "pack_regather", "combine") if kname in kernels]
+        dom = max(movers, key=lambda kname: kernels[kname]["us_per_step"])
+        achieved = per_launch[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e9
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):
+            try:
+                tj = json.load(open(tpath))
+                traffic = tj.get(f"{w.name}/S{w.slices}/mode{mode}", {}).get(dom)
+            except (OSError, ValueError):
+                traffic = None
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                    "bytes_per_launch": int(per_launch[dom]), "avg_launch_us": round(kernels[dom]["avg_us"], 2),
+                    "traffic": traffic}
+        for kname in movers:
+            kernels[kname]["GBps"] = round(per_launch[kname] / (kernels[kname]["avg_us"] * 1e-6) / 1e9, 1)
+        for v in kernels.values():
+            for kk in list(v):
+                v[kk] = round(v[kk], 3)
+
+    # ---- CPU oracle on this host (a baseline for context, never the target)
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        reps, spent = 0, 0.0
+        budget = 12.0
+        while reps < 20 and spent < budget:
+            c0 = time.perf_counter()
+            oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm)
+            spent += time.perf_counter() - c0
+            reps += 1
+        cpu = {"value": round(w.tokens * reps / spent, 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+               "sample": f"the whole {w.name} workload, {reps} passes of the single-threaded C oracle, {spent:.1f} s",
+               "effective_GBps": round(ab["total"] * reps / spent / 1e9, 2)}
+
+    line = {
+        "metric": "dispatch+combine tokens/s", "value": round(tokens_per_s, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == workloads.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "tokens": w.tokens, "hidden": w.hidden, "experts": w.experts,
+                   "top_k": w.top_k, "ep": w.ep, "tp": w.tp, "slices": w.slices,
+                   "capacity_factor": w.capacity_factor, "kept_rows": ab["R"], "alive_tokens": ab["alive"],
+                   "pipeline_mode": mode, "hip_graph": use_graph, "parallelism": "1 GPU, virtual ep/tp"},
+        "effective_GBps": round(eff_gbps, 1), "pct_of_hbm_peak": round(100 * eff_gbps / HBM_PEAK_GBPS, 2),
+        "algorithmic_bytes_per_step": int(ab["total"]),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,200 @@
+/*
+ * monta.h -- C ABI of the MI355X (gfx950) MoE token dispatch / combine path of
+ * MoNTA (arxiv 2411.00662).
+ *
+ * One GPU holds what the paper spreads over an expert-parallel (EP) x
+ * tensor-parallel (TP) group: the `ep` destination ranks and the `tp` redundant
+ * TP ranks are *virtual* -- partitions of buffers in one HBM allocation.  The
+ * path is the source-side work of the paper's first AllToAll and its mirror:
+ *
+ *   route     gate logits -> top-k expert ids + probabilities          (section "Expert Parallel": Routing)
+ *   plan      stable counting sort of (token, choice) pairs by expert   (same section: Permutation)
+ *   dispatch  each virtual TP rank packs only its 1/tp of the tokens of (section "Pipelining": "Drop" split;
+ *             slice j into its region of the send buffer STAGE           Eq. 4: chunks along the sequence)
+ *   regather  every (unit, expert) block of STAGE is copied to its      (section "Pipelining": AllGather; paragraph
+ *             place in the expert-major buffer FINAL                     "AllGather and D2D copy Pipelining")
+ *   combine   out[t] = sum_j gate[t,j] * y[row of (t,j)]                (section "Expert Parallel": Combine, Unpermutation)
+ *
+ * FINAL is, byte for byte, what the plain (tp = 1, slices = 1) permutation
+ * produces: the paper's claim that its transforms are exact rearrangements.
+ *
+ * Conventions
+ *   - Every pointer except `cfg`, `layout` and output scalars is a DEVICE pointer
+ *     owned by the caller.  The library allocates no user buffer and frees none.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     only enqueue work; none synchronises with the host.
+ *   - Return value: MONTA_OK (0) or a negative monta_status.  Arguments are
+ *     validated before the first HIP call, so bad arguments never reach the GPU.
+ *     Nothing throws or aborts across this boundary.
+ *   - Limits: 1 <= top_k <= experts <= 256, top_k <= 32, experts % ep == 0,
+ *     tokens % (slices * tp) == 0, tokens * top_k < 2^31,
+ *     hidden * sizeof(element) % 16 == 0; activation base pointers 16-byte
+ *     aligned, all others 4-byte aligned.  Logits must be finite (NaN is
+ *     treated as -inf; the result is then unspecified but in bounds).
+ *
+ * Units.  U = slices * tp units of Tu = tokens / U consecutive tokens; unit u is
+ * slice u / tp, virtual TP rank u % tp.  Expert e lives on virtual EP rank
+ * e / (experts / ep), so expert order is (EP rank, local expert) order.
+ *
+ * Buffers.  STAGE and FINAL hold `max_rows` rows of hidden elements; only rows
+ * below R (the number of kept pairs) are ever written.
+ *   STAGE  [slice][tp rank][expert][kept rows of that unit, token order]
+ *   FINAL  [expert][kept rows, token order]
+ */
+#ifndef MONTA_H
+#define MONTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum monta_dtype { MONTA_FP32 = 0, MONTA_BF16 = 1 };
+
+enum monta_status {
+    MONTA_OK = 0,
+    MONTA_ERR_INVALID = -1,     /* a size or flag violates the preconditions above          */
+    MONTA_ERR_UNSUPPORTED = -2, /* valid in principle, outside this library's limits        */
+    MONTA_ERR_NULL = -3,        /* a required pointer is NULL                               */
+    MONTA_ERR_HIP = -4,         /* a HIP runtime call failed; see monta_last_hip_error()    */
+    MONTA_ERR_ALIGN = -5        /* a pointer is not aligned as required                     */
+};
+
+/* The problem statement: tokens, hidden, experts, top-k, ep, tp, slices, capacity. */
+typedef struct monta_cfg {
+    int64_t tokens;          /* T = microbatch * sequence length (b*s of Eq. 3)               */
+    int32_t hidden;          /* H, elements per token row                                       */
+    int32_t dtype;           /* monta_dtype of activations; logits and gates are always fp32    */
+    int32_t experts;         /* E                                                               */
+    int32_t top_k;           /* k                                                               */
+    int32_t ep;              /* virtual expert-parallel ranks (e of Eq. 8)                      */
+    int32_t tp;              /* virtual tensor-parallel ranks (t of Eq. 8-9)                    */
+    int32_t slices;          /* S chunks along the sequence (N of Eq. 4)                        */
+    float capacity_factor;   /* 0: nothing is dropped; else C = min(T, ceil(cf*T*k/E)) per expert,
+                                global over all tokens, lowest token indices survive            */
+    int32_t renorm;          /* 1: gates renormalised over the k winners; 0: softmax over all E */
+} monta_cfg;
+
+/* Where the plan tables live inside the caller's workspace (byte offsets from
+ * `ws`; every table is int32, row-major).  Filled by monta_ws_layout_query(). */
+typedef struct monta_ws_layout {
+    int64_t ws_bytes;        /* size the caller must allocate (256-byte aligned base)           */
+    int64_t max_rows;        /* rows STAGE / FINAL / expert output must hold: min(T*k, E*C)     */
+    int64_t capacity;        /* C                                                               */
+    int32_t units;           /* U                                                               */
+    int32_t tokens_per_unit; /* Tu                                                              */
+    int32_t block_tokens;    /* tokens routed per workgroup (internal granularity)             */
+    int32_t num_blocks;      /* workgroups of the route kernel                                  */
+    int64_t off_meta;        /* [16]: [0] R  [1] tokens with >= 1 kept pair  [2] C  (rest internal) */
+    int64_t off_counts;      /* [E]     pairs that chose expert e                               */
+    int64_t off_kept;        /* [E]     min(counts, C)                                          */
+    int64_t off_offsets;     /* [E+1]   exclusive scan of kept; offsets[E] = R                  */
+    int64_t off_n;           /* [U][E]  kept pairs of expert e with token in unit u             */
+    int64_t off_stage_off;   /* [U][E]  first STAGE row of block (u,e)                          */
+    int64_t off_unit_base;   /* [U][E]  first FINAL row of block (u,e)                          */
+    int64_t off_send_rows;   /* [U][ep] rows unit u addresses to virtual EP rank d              */
+    int64_t off_unit_rows;   /* [U+1]   first STAGE row of unit u; [U] = R                      */
+    int64_t off_pos_final;   /* [T][k]  FINAL row of pair (t,j), -1 if dropped                  */
+    int64_t off_pos_stage;   /* [T][k]  STAGE row of pair (t,j), -1 if dropped                  */
+    int64_t off_row_map;     /* [max_rows] FINAL row of STAGE row s (the per-row index offsets) */
+    int64_t off_block_counts;/* [num_blocks][E] internal                                        */
+    int64_t off_block_base;  /* [num_blocks][E] internal                                        */
+} monta_ws_layout;
+
+/* Host only.  Validates cfg and reports the workspace size and the row capacity
+ * the activation buffers need. */
+int monta_workspace_bytes(const monta_cfg *cfg, size_t *ws_bytes, int64_t *max_rows);
+
+/* Host only.  Same validation; fills the whole layout. */
+int monta_ws_layout_query(const monta_cfg *cfg, monta_ws_layout *layout);
+
+/* Puts a freshly allocated workspace into its initial state (a small fill kernel
+ * on `stream`; zero-filling the workspace by any other means is equivalent).
+ * Needed once per workspace, before its first monta_route. */
+int monta_ws_init(const monta_cfg *cfg, void *ws, void *stream);
+
+/* Routing + Permutation plan.  logits [T][E] fp32 -> topk_idx [T][k] int32 (slot 0
+ * = strongest choice; ties go to the lower expert index; selection is on the raw
+ * logits), gates [T][k] fp32 (evaluated in fp64, rounded once), and every plan
+ * table of monta_ws_layout in `ws`.  `ws` must be ws_bytes large and must have
+ * been through monta_ws_init once (the library keeps it consistent from then on).  Calls on the same ws must not overlap in time. */
+int monta_route(const monta_cfg *cfg, const float *logits, int32_t *topk_idx, float *gates,
+                void *ws, void *stream);
+
+/* Send-buffer packing with the TP-group split and the sequence chunks: for every
+ * token of slice `slice` (all slices if -1) and every kept choice j the token's row
+ * is copied, bit for bit, to STAGE row pos_stage[t][j].  x [T][H], stage
+ * [max_rows][H] in cfg->dtype.  Needs the tables written by monta_route on `ws`.
+ * Per virtual TP rank and slice this moves T*k*row/(S*tp) bytes when nothing is
+ * dropped: the I/(N*t) of Eq. 8. */
+int monta_dispatch(const monta_cfg *cfg, const void *x, void *stage, const void *ws, int slice,
+                   void *stream);
+
+/* Intra-node gather + D2D copy to index offsets, as one device copy pass:
+ * STAGE row s of slice `slice` (all if -1) goes to FINAL row row_map[s].  After
+ * all slices FINAL[pos_final[t][j]] == x[t] for every kept pair. */
+int monta_regather(const monta_cfg *cfg, const void *stage, void *final_, const void *ws, int slice,
+                   void *stream);
+
+/* The slice pipeline (the paper's multi-stream schedule, section "AllToAll
+ * performance", Implementation): regather(j) runs after pack(j) and overlaps
+ * pack(j+1); everything has finished, in stream order, when the call's work on
+ * `stream` completes.  Equivalent to calling monta_dispatch and monta_regather
+ * for j = 0..S-1.  How the overlap is realised is chosen by
+ * monta_set_pipeline_mode(). */
+int monta_dispatch_regather(const monta_cfg *cfg, const void *x, void *stage, void *final_,
+                            const void *ws, void *stream);
+
+/* Unpermutation with scale-add: out[t][:] = sum over kept j (ascending) of
+ * gates[t][j] * y[pos_final[t][j]][:], accumulated in fp32 with fused
+ * multiply-adds and rounded once (nearest-even) to cfg->dtype; a token with no
+ * kept pair gives a zero row.  y [max_rows][H] is the expert output in FINAL
+ * layout (FINAL itself under identity experts), out [T][H]. */
+int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void *out, const void *ws,
+                  void *stream);
+
+/* Pipeline realisations for monta_dispatch_regather:
+ *   0  two streams: packs on `stream`, regathers on a library-owned side stream
+ *      (default priority), one event per slice, joined back into `stream`;
+ *   1  one stream, co-scheduled grids: launch j does regather(j-1) and pack(j) in
+ *      disjoint workgroups of one grid (S+1 launches, no events);
+ *   2  one stream, strictly serial pack(0), regather(0), pack(1), ...
+ * Returns MONTA_ERR_INVALID for other values.  Process-wide; default 1. */
+int monta_set_pipeline_mode(int mode);
+int monta_get_pipeline_mode(void);
+
+/* Plain device copy of `bytes` (multiple of 16, 16-byte aligned pointers) with the
+ * same 16-byte-per-lane access pattern as the row movers.  It exists to measure
+ * the achievable copy bandwidth and to calibrate profiler byte counters. */
+int monta_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/* Per-kernel timing with HIP events recorded on the launching stream.
+ * monta_profile_enable(1) starts bracketing every kernel launch; monta_profile_read
+ * synchronises with the recorded events and returns the summed duration and the
+ * launch count of one kernel class since the last reset.  Meant for benchmarks:
+ * bracketing adds host work per launch. */
+enum monta_kernel_id {
+    MONTA_K_ROUTE = 0,      /* top-k + gates + histogram + scan               */
+    MONTA_K_POSITIONS = 1,  /* per-pair positions and row map                 */
+    MONTA_K_PACK = 2,
+    MONTA_K_REGATHER = 3,
+    MONTA_K_PACK_REGATHER = 4, /* co-scheduled grid of pipeline mode 1        */
+    MONTA_K_COMBINE = 5,
+    MONTA_K_COPY = 6,
+    MONTA_K_COUNT = 7
+};
+int monta_profile_enable(int on);
+int monta_profile_reset(void);
+int monta_profile_read(int kernel_id, double *total_ms, int64_t *launches);
+
+/* Text for a monta_status; never NULL. */
+const char *monta_strerror(int code);
+/* The hipError_t (as int) behind the calling thread's last MONTA_ERR_HIP, 0 if none. */
+int monta_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MONTA_H */

@@ -1,0 +1,219 @@
+"""ctypes binding of the C ABI in include/monta.h.
+
+Argument marshalling only: every function here has the name and the argument
+order of its C counterpart, turns torch tensors into raw device pointers, checks
+that the tensors are large enough for the shapes in ``cfg`` (the C side sees
+only pointers), and raises ``MontaError`` on a negative status.  No step of the
+path runs in Python, and there is no fallback: if ``libmonta.so`` has not been
+built, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmonta.so")
+
+FP32, BF16 = 0, 1
+K_ROUTE, K_POSITIONS, K_PACK, K_REGATHER, K_PACK_REGATHER, K_COMBINE, K_COPY = range(7)
+KERNEL_NAMES = ["route_plan", "positions", "pack", "regather", "pack_regather", "combine", "copy"]
+
+
+class MontaError(RuntimeError):
+    def __init__(self, code: int, what: str, detail: str = ""):
+        self.code = code
+        super().__init__(f"{what}: {detail} (status {code})")
+
+
+class monta_cfg(ctypes.Structure):
+    _fields_ = [("tokens", ctypes.c_int64), ("hidden", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("experts", ctypes.c_int32), ("top_k", ctypes.c_int32), ("ep", ctypes.c_int32),
+                ("tp", ctypes.c_int32), ("slices", ctypes.c_int32), ("capacity_factor", ctypes.c_float),
+                ("renorm", ctypes.c_int32)]
+
+
+class monta_ws_layout(ctypes.Structure):
+    _fields_ = [("ws_bytes", ctypes.c_int64), ("max_rows", ctypes.c_int64), ("capacity", ctypes.c_int64),
+                ("units", ctypes.c_int32), ("tokens_per_unit", ctypes.c_int32), ("block_tokens", ctypes.c_int32),
+                ("num_blocks", ctypes.c_int32),
+                ("off_meta", ctypes.c_int64), ("off_counts", ctypes.c_int64), ("off_kept", ctypes.c_int64),
+                ("off_offsets", ctypes.c_int64), ("off_n", ctypes.c_int64), ("off_stage_off", ctypes.c_int64),
+                ("off_unit_base", ctypes.c_int64), ("off_send_rows", ctypes.c_int64),
+                ("off_unit_rows", ctypes.c_int64), ("off_pos_final", ctypes.c_int64),
+                ("off_pos_stage", ctypes.c_int64), ("off_row_map", ctypes.c_int64),
+                ("off_block_counts", ctypes.c_int64), ("off_block_base", ctypes.c_int64)]
+
+
+# every symbol include/monta.h declares
+EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "monta_route", "monta_dispatch",
+           "monta_regather", "monta_dispatch_regather", "monta_combine", "monta_set_pipeline_mode",
+           "monta_get_pipeline_mode", "monta_copy", "monta_profile_enable", "monta_profile_reset",
+           "monta_profile_read", "monta_strerror", "monta_last_hip_error"]
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2411_00662_amd.build); "
+                               "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64p = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)
+        cfgp = ctypes.POINTER(monta_cfg)
+        L.monta_workspace_bytes.argtypes = [cfgp, ctypes.POINTER(ctypes.c_size_t), i64p]
+        L.monta_ws_layout_query.argtypes = [cfgp, ctypes.POINTER(monta_ws_layout)]
+        L.monta_ws_init.argtypes = [cfgp, vp, vp]
+        L.monta_route.argtypes = [cfgp, vp, vp, vp, vp, vp]
+        L.monta_dispatch.argtypes = [cfgp, vp, vp, vp, i32, vp]
+        L.monta_regather.argtypes = [cfgp, vp, vp, vp, i32, vp]
+        L.monta_dispatch_regather.argtypes = [cfgp, vp, vp, vp, vp, vp]
+        L.monta_combine.argtypes = [cfgp, vp, vp, vp, vp, vp]
+        L.monta_set_pipeline_mode.argtypes = [i32]
+        L.monta_get_pipeline_mode.argtypes = []
+        L.monta_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.monta_profile_enable.argtypes = [i32]
+        L.monta_profile_reset.argtypes = []
+        L.monta_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), i64p]
+        L.monta_strerror.argtypes = [i32]
+        L.monta_strerror.restype = ctypes.c_char_p
+        L.monta_last_hip_error.argtypes = []
+        for name in EXPORTS:
+            if name != "monta_strerror":
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def monta_strerror(code: int) -> str:
+    return lib().monta_strerror(int(code)).decode()
+
+
+def monta_last_hip_error() -> int:
+    return int(lib().monta_last_hip_error())
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        detail = monta_strerror(code)
+        if code == -4:
+            detail += f", hipError_t {monta_last_hip_error()}"
+        raise MontaError(code, what, detail)
+
+
+def make_cfg(tokens, hidden, dtype, experts, top_k, ep, tp, slices, capacity_factor=0.0, renorm=1) -> monta_cfg:
+    return monta_cfg(int(tokens), int(hidden), int(dtype), int(experts), int(top_k), int(ep), int(tp), int(slices),
+                     float(capacity_factor), int(renorm))
+
+
+def _bpe(cfg) -> int:
+    return 4 if cfg.dtype == FP32 else 2
+
+
+def _ptr(t, min_bytes: int, name: str) -> int:
+    """Raw pointer of a torch tensor (or an int address, passed through unchecked)."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise ValueError(f"{name}: expected a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: expected a contiguous tensor")
+    have = t.numel() * t.element_size()
+    if have < min_bytes:
+        raise ValueError(f"{name}: tensor holds {have} bytes, the shapes in cfg need {min_bytes}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def monta_workspace_bytes(cfg):
+    ws, rows = ctypes.c_size_t(0), ctypes.c_int64(0)
+    _check(lib().monta_workspace_bytes(ctypes.byref(cfg), ctypes.byref(ws), ctypes.byref(rows)), "monta_workspace_bytes")
+    return int(ws.value), int(rows.value)
+
+
+def monta_ws_layout_query(cfg) -> monta_ws_layout:
+    L = monta_ws_layout()
+    _check(lib().monta_ws_layout_query(ctypes.byref(cfg), ctypes.byref(L)), "monta_ws_layout_query")
+    return L
+
+
+def monta_ws_init(cfg, ws, stream=None):
+    L = monta_ws_layout_query(cfg)
+    _check(lib().monta_ws_init(ctypes.byref(cfg), _ptr(ws, L.ws_bytes, "ws"), _stream(stream)), "monta_ws_init")
+
+
+def monta_route(cfg, logits, topk_idx, gates, ws, stream=None):
+    L = monta_ws_layout_query(cfg)
+    T, E, k = cfg.tokens, cfg.experts, cfg.top_k
+    _check(lib().monta_route(ctypes.byref(cfg), _ptr(logits, T * E * 4, "logits"), _ptr(topk_idx, T * k * 4, "topk_idx"),
+                             _ptr(gates, T * k * 4, "gates"), _ptr(ws, L.ws_bytes, "ws"), _stream(stream)),
+           "monta_route")
+
+
+def monta_dispatch(cfg, x, stage, ws, slice=-1, stream=None):
+    L = monta_ws_layout_query(cfg)
+    row = cfg.hidden * _bpe(cfg)
+    _check(lib().monta_dispatch(ctypes.byref(cfg), _ptr(x, cfg.tokens * row, "x"), _ptr(stage, L.max_rows * row, "stage"),
+                                _ptr(ws, L.ws_bytes, "ws"), int(slice), _stream(stream)), "monta_dispatch")
+
+
+def monta_regather(cfg, stage, final_, ws, slice=-1, stream=None):
+    L = monta_ws_layout_query(cfg)
+    row = cfg.hidden * _bpe(cfg)
+    _check(lib().monta_regather(ctypes.byref(cfg), _ptr(stage, L.max_rows * row, "stage"),
+                                _ptr(final_, L.max_rows * row, "final_"), _ptr(ws, L.ws_bytes, "ws"), int(slice),
+                                _stream(stream)), "monta_regather")
+
+
+def monta_dispatch_regather(cfg, x, stage, final_, ws, stream=None):
+    L = monta_ws_layout_query(cfg)
+    row = cfg.hidden * _bpe(cfg)
+    _check(lib().monta_dispatch_regather(ctypes.byref(cfg), _ptr(x, cfg.tokens * row, "x"),
+                                         _ptr(stage, L.max_rows * row, "stage"), _ptr(final_, L.max_rows * row, "final_"),
+                                         _ptr(ws, L.ws_bytes, "ws"), _stream(stream)), "monta_dispatch_regather")
+
+
+def monta_combine(cfg, y, gates, out, ws, stream=None):
+    L = monta_ws_layout_query(cfg)
+    row = cfg.hidden * _bpe(cfg)
+    _check(lib().monta_combine(ctypes.byref(cfg), _ptr(y, L.max_rows * row, "y"),
+                               _ptr(gates, cfg.tokens * cfg.top_k * 4, "gates"), _ptr(out, cfg.tokens * row, "out"),
+                               _ptr(ws, L.ws_bytes, "ws"), _stream(stream)), "monta_combine")
+
+
+def monta_set_pipeline_mode(mode: int):
+    _check(lib().monta_set_pipeline_mode(int(mode)), "monta_set_pipeline_mode")
+
+
+def monta_get_pipeline_mode() -> int:
+    return int(lib().monta_get_pipeline_mode())
+
+
+def monta_copy(dst, src, nbytes: int, stream=None):
+    _check(lib().monta_copy(_ptr(dst, nbytes, "dst"), _ptr(src, nbytes, "src"), int(nbytes), _stream(stream)), "monta_copy")
+
+
+def monta_profile_enable(on: bool):
+    _check(lib().monta_profile_enable(1 if on else 0), "monta_profile_enable")
+
+
+def monta_profile_reset():
+    _check(lib().monta_profile_reset(), "monta_profile_reset")
+
+
+def monta_profile_read(kernel_id: int):
+    ms, n = ctypes.c_double(0), ctypes.c_int64(0)
+    _check(lib().monta_profile_read(int(kernel_id), ctypes.byref(ms), ctypes.byref(n)), "monta_profile_read")
+    return float(ms.value), int(n.value)

@@ -1,0 +1,554 @@
+// Host side of the C ABI declared in include/monta.h: argument validation,
+// workspace layout, launch shapes, the slice pipeline and event profiling.
+// Everything that touches data runs in the kernels of monta_kernels.hpp.
+#include "monta.h"
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "monta_kernels.hpp"
+
+namespace {
+
+using namespace monta;
+
+thread_local int g_last_hip = 0;
+std::atomic<int> g_pipeline_mode{1};
+
+#define HIP_TRY(expr)                          \
+    do {                                       \
+        hipError_t e__ = (expr);               \
+        if (e__ != hipSuccess) {               \
+            g_last_hip = (int)e__;             \
+            (void)hipGetLastError();           \
+            return MONTA_ERR_HIP;              \
+        }                                      \
+    } while (0)
+
+inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+int pow2ceil(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+struct Geometry {
+    Shape s;
+    int64_t max_rows;
+    int64_t row_bytes;
+    size_t route_lds;
+    int route_threads;
+};
+
+// Per-expert capacity: C = min(T, ceil(cf*T*k/E)), cf = 0 meaning "no drop".
+int64_t capacity_of(const monta_cfg *c)
+{
+    if (c->capacity_factor <= 0.f) return c->tokens;
+    double v = std::ceil((double)c->capacity_factor * (double)c->tokens * (double)c->top_k / (double)c->experts);
+    if (v > (double)c->tokens) return c->tokens;
+    return (int64_t)v;
+}
+
+size_t route_lds_bytes(int TB, int E, int k)
+{
+    const int NW = TB > kWave ? TB / kWave : 1;
+    size_t b = ((size_t)TB * (E | 1) * 4 + (size_t)TB * k * 4 + 7) & ~(size_t)7;
+    return b + (size_t)E * NW * 8;
+}
+
+int validate(const monta_cfg *c, Geometry *g)
+{
+    if (!c) return MONTA_ERR_NULL;
+    if (c->tokens < 1 || c->hidden < 1 || c->experts < 1 || c->top_k < 1 || c->ep < 1 || c->tp < 1 || c->slices < 1)
+        return MONTA_ERR_INVALID;
+    if (c->dtype != MONTA_FP32 && c->dtype != MONTA_BF16) return MONTA_ERR_INVALID;
+    if (c->renorm != 0 && c->renorm != 1) return MONTA_ERR_INVALID;
+    if (c->top_k > c->experts) return MONTA_ERR_INVALID;
+    if (c->experts % c->ep != 0) return MONTA_ERR_INVALID;
+    if (!(c->capacity_factor >= 0.f) || !std::isfinite(c->capacity_factor)) return MONTA_ERR_INVALID;
+    const int64_t U = (int64_t)c->slices * c->tp;
+    if (c->tokens % U != 0) return MONTA_ERR_INVALID;
+    const int64_t row = (int64_t)c->hidden * (c->dtype == MONTA_FP32 ? 4 : 2);
+    if (row % 16 != 0) return MONTA_ERR_INVALID;
+    if (c->experts > 256 || c->top_k > 32) return MONTA_ERR_UNSUPPORTED;
+    if (c->tokens * (int64_t)c->top_k > 0x7fffffffLL) return MONTA_ERR_UNSUPPORTED;
+    if (row / 16 > 0x7fffffffLL || U * c->experts > 0x7fffffffLL) return MONTA_ERR_UNSUPPORTED;
+
+    Shape &s = g->s;
+    s.T = (int32_t)c->tokens;
+    s.E = c->experts;
+    s.k = c->top_k;
+    s.ep = c->ep;
+    s.tp = c->tp;
+    s.S = c->slices;
+    s.U = (int32_t)U;
+    s.Tu = (int32_t)(c->tokens / U);
+    s.C = (int32_t)capacity_of(c);
+    s.renorm = c->renorm;
+    s.vpr = (int32_t)(row / 16);
+    s.lpr = pow2ceil(s.vpr) < kMoverThreads ? pow2ceil(s.vpr) : kMoverThreads;
+    // route workgroup: as many tokens as fit 60 KiB of LDS, at most 256, no more than a unit needs
+    int TB = 256;
+    while (TB > 32 && (route_lds_bytes(TB, s.E, s.k) > 60 * 1024 || TB / 2 >= s.Tu)) TB >>= 1;
+    if (route_lds_bytes(TB, s.E, s.k) > 60 * 1024) return MONTA_ERR_UNSUPPORTED;
+    s.TB = TB;
+    s.bpu = (s.Tu + TB - 1) / TB;
+    const int64_t nb = (int64_t)s.bpu * U;
+    if (nb * s.E > 0x7fffffffLL) return MONTA_ERR_UNSUPPORTED;
+    s.num_blocks = (int32_t)nb;
+    g->route_lds = route_lds_bytes(TB, s.E, s.k);
+    g->route_threads = TB < kWave ? kWave : TB;
+    const int64_t tk = c->tokens * (int64_t)c->top_k, ec = (int64_t)c->experts * s.C;
+    g->max_rows = tk < ec ? tk : ec;
+    s.max_rows = (int32_t)g->max_rows;
+    g->row_bytes = row;
+    return MONTA_OK;
+}
+
+void fill_layout(const Geometry &g, monta_ws_layout *L)
+{
+    const Shape &s = g.s;
+    int64_t off = 0;
+    auto take = [&](int64_t ints) {
+        int64_t o = off;
+        off = align_up(off + ints * 4, 256);
+        return o;
+    };
+    L->max_rows = g.max_rows;
+    L->capacity = s.C;
+    L->units = s.U;
+    L->tokens_per_unit = s.Tu;
+    L->block_tokens = s.TB;
+    L->num_blocks = s.num_blocks;
+    L->off_meta = take(META_SLOTS);
+    L->off_counts = take(s.E);
+    L->off_kept = take(s.E);
+    L->off_offsets = take(s.E + 1);
+    L->off_n = take((int64_t)s.U * s.E);
+    L->off_stage_off = take((int64_t)s.U * s.E);
+    L->off_unit_base = take((int64_t)s.U * s.E);
+    L->off_send_rows = take((int64_t)s.U * s.ep);
+    L->off_unit_rows = take((int64_t)s.U + 1);
+    L->off_pos_final = take((int64_t)s.T * s.k);
+    L->off_pos_stage = take((int64_t)s.T * s.k);
+    L->off_row_map = take(g.max_rows);
+    L->off_block_counts = take((int64_t)s.num_blocks * s.E);
+    L->off_block_base = take((int64_t)s.num_blocks * s.E);
+    L->ws_bytes = off;
+}
+
+PlanPtrs plan_ptrs(const Geometry &g, const void *ws)
+{
+    monta_ws_layout L;
+    fill_layout(g, &L);
+    char *b = const_cast<char *>(static_cast<const char *>(ws));
+    auto at = [&](int64_t o) { return reinterpret_cast<int32_t *>(b + o); };
+    PlanPtrs p;
+    p.meta = at(L.off_meta);
+    p.counts = at(L.off_counts);
+    p.kept = at(L.off_kept);
+    p.offsets = at(L.off_offsets);
+    p.n = at(L.off_n);
+    p.stage_off = at(L.off_stage_off);
+    p.unit_base = at(L.off_unit_base);
+    p.send_rows = at(L.off_send_rows);
+    p.unit_rows = at(L.off_unit_rows);
+    p.pos_final = at(L.off_pos_final);
+    p.pos_stage = at(L.off_pos_stage);
+    p.row_map = at(L.off_row_map);
+    p.block_counts = at(L.off_block_counts);
+    p.block_base = at(L.off_block_base);
+    return p;
+}
+
+inline bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+// ------------------------------------------------------------- profiling
+
+struct ProfRec {
+    int kid;
+    hipEvent_t a, b;
+};
+std::mutex g_prof_mu;
+std::atomic<int> g_prof_on{0};
+std::vector<ProfRec> g_prof_recs;
+double g_prof_ms[MONTA_K_COUNT] = {0};
+int64_t g_prof_n[MONTA_K_COUNT] = {0};
+
+struct ProfScope {
+    hipStream_t st;
+    int kid;
+    hipEvent_t a = nullptr, b = nullptr;
+    bool on;
+    ProfScope(int kid_, hipStream_t st_) : st(st_), kid(kid_), on(g_prof_on.load() != 0)
+    {
+        if (!on) return;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+            on = false;
+            return;
+        }
+        (void)hipEventRecord(a, st);
+    }
+    ~ProfScope()
+    {
+        if (!on) return;
+        (void)hipEventRecord(b, st);
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof_recs.push_back({kid, a, b});
+    }
+};
+
+int prof_drain()
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    int rc = MONTA_OK;
+    for (auto &r : g_prof_recs) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(r.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);
+        if (e == hipSuccess) {
+            g_prof_ms[r.kid] += ms;
+            g_prof_n[r.kid] += 1;
+        } else {
+            g_last_hip = (int)e;
+            rc = MONTA_ERR_HIP;
+        }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_prof_recs.clear();
+    return rc;
+}
+
+// ------------------------------------------------- side stream for mode 0
+
+struct DevState {
+    hipStream_t side = nullptr;
+    std::vector<hipEvent_t> ev;
+    hipEvent_t done = nullptr;
+};
+std::mutex g_dev_mu;
+DevState g_dev[64];
+
+int dev_state(int nslices, DevState **out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return MONTA_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lk(g_dev_mu);
+    DevState &d = g_dev[dev];
+    if (!d.side) HIP_TRY(hipStreamCreateWithFlags(&d.side, hipStreamNonBlocking));
+    if (!d.done) HIP_TRY(hipEventCreateWithFlags(&d.done, hipEventDisableTiming));
+    while ((int)d.ev.size() < nslices) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        d.ev.push_back(e);
+    }
+    *out = &d;
+    return MONTA_OK;
+}
+
+// ------------------------------------------------------------ launch shapes
+
+constexpr int kMaxMoverGrid = 1 << 16;
+
+int mover_grid(const Shape &s, int64_t rows)
+{
+    const int rows_per_wg = kMoverThreads / s.lpr;
+    int64_t g = (rows + rows_per_wg - 1) / rows_per_wg;
+    if (g < 1) g = 1;
+    if (g > kMaxMoverGrid) g = kMaxMoverGrid;
+    return (int)g;
+}
+
+int64_t slice_rows_bound(const Geometry &g, int nslices_covered)
+{
+    int64_t r = (int64_t)g.s.tp * g.s.Tu * nslices_covered * g.s.k;
+    return r < g.max_rows ? r : g.max_rows;
+}
+
+int launch_pack(const Geometry &g, const PlanPtrs &p, const void *x, void *stage, int slice, hipStream_t st)
+{
+    const Shape &s = g.s;
+    const int per_slice = s.tp * s.Tu;
+    const int t0 = slice < 0 ? 0 : slice * per_slice;
+    const int nt = slice < 0 ? s.T : per_slice;
+    ProfScope ps(MONTA_K_PACK, st);
+    hipLaunchKernelGGL(pack_kernel, dim3(mover_grid(s, nt)), dim3(kMoverThreads), 0, st,
+                       static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), p, s, t0, nt);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+int launch_regather(const Geometry &g, const PlanPtrs &p, const void *stage, void *fin, int slice, hipStream_t st)
+{
+    const Shape &s = g.s;
+    const int u0 = slice < 0 ? 0 : slice * s.tp;
+    const int u1 = slice < 0 ? s.U : (slice + 1) * s.tp;
+    const int64_t bound = slice_rows_bound(g, slice < 0 ? s.S : 1);
+    ProfScope ps(MONTA_K_REGATHER, st);
+    hipLaunchKernelGGL(regather_kernel, dim3(mover_grid(s, bound)), dim3(kMoverThreads), 0, st,
+                       static_cast<const u32x4 *>(stage), static_cast<u32x4 *>(fin), p, s, u0, u1);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+int launch_pack_regather(const Geometry &g, const PlanPtrs &p, const void *x, void *stage, void *fin, int slice,
+                         hipStream_t st)
+{
+    // packs `slice`, regathers `slice - 1`
+    const Shape &s = g.s;
+    const int per_slice = s.tp * s.Tu;
+    const int n_pack = mover_grid(s, per_slice);
+    const int n_reg = mover_grid(s, slice_rows_bound(g, 1));
+    ProfScope ps(MONTA_K_PACK_REGATHER, st);
+    hipLaunchKernelGGL(pack_regather_kernel, dim3(n_pack + n_reg), dim3(kMoverThreads), 0, st,
+                       static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), static_cast<u32x4 *>(fin), p, s,
+                       slice * per_slice, per_slice, (slice - 1) * s.tp, slice * s.tp, n_pack);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+int check_act_ptrs(const void *a, const void *b)
+{
+    if (!a || !b) return MONTA_ERR_NULL;
+    if (misaligned(a, 16) || misaligned(b, 16)) return MONTA_ERR_ALIGN;
+    return MONTA_OK;
+}
+
+int check_ws(const void *ws)
+{
+    if (!ws) return MONTA_ERR_NULL;
+    if (misaligned(ws, 16)) return MONTA_ERR_ALIGN;
+    return MONTA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int monta_workspace_bytes(const monta_cfg *cfg, size_t *ws_bytes, int64_t *max_rows)
+{
+    if (!ws_bytes || !max_rows) return MONTA_ERR_NULL;
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    monta_ws_layout L;
+    fill_layout(g, &L);
+    *ws_bytes = (size_t)L.ws_bytes;
+    *max_rows = L.max_rows;
+    return MONTA_OK;
+}
+
+int monta_ws_layout_query(const monta_cfg *cfg, monta_ws_layout *layout)
+{
+    if (!layout) return MONTA_ERR_NULL;
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    fill_layout(g, layout);
+    return MONTA_OK;
+}
+
+int monta_ws_init(const monta_cfg *cfg, void *ws, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if ((rc = check_ws(ws))) return rc;
+    PlanPtrs p = plan_ptrs(g, ws);
+    hipLaunchKernelGGL(ws_init_kernel, dim3(1), dim3(kWave), 0, static_cast<hipStream_t>(stream), p.meta);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+int monta_route(const monta_cfg *cfg, const float *logits, int32_t *topk_idx, float *gates, void *ws, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (!logits || !topk_idx || !gates) return MONTA_ERR_NULL;
+    if (misaligned(logits, 4) || misaligned(topk_idx, 4) || misaligned(gates, 4)) return MONTA_ERR_ALIGN;
+    if ((rc = check_ws(ws))) return rc;
+    const Shape &s = g.s;
+    PlanPtrs p = plan_ptrs(g, ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        ProfScope ps(MONTA_K_ROUTE, st);
+        hipLaunchKernelGGL(route_plan_kernel, dim3(s.num_blocks), dim3(g.route_threads), g.route_lds, st, logits,
+                           topk_idx, gates, p, s);
+        HIP_TRY(hipGetLastError());
+    }
+    {
+        ProfScope ps(MONTA_K_POSITIONS, st);
+        hipLaunchKernelGGL(positions_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, topk_idx, p, s);
+        HIP_TRY(hipGetLastError());
+    }
+    return MONTA_OK;
+}
+
+int monta_dispatch(const monta_cfg *cfg, const void *x, void *stage, const void *ws, int slice, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (slice < -1 || slice >= cfg->slices) return MONTA_ERR_INVALID;
+    if ((rc = check_act_ptrs(x, stage))) return rc;
+    if ((rc = check_ws(ws))) return rc;
+    return launch_pack(g, plan_ptrs(g, ws), x, stage, slice, static_cast<hipStream_t>(stream));
+}
+
+int monta_regather(const monta_cfg *cfg, const void *stage, void *final_, const void *ws, int slice, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (slice < -1 || slice >= cfg->slices) return MONTA_ERR_INVALID;
+    if ((rc = check_act_ptrs(stage, final_))) return rc;
+    if (stage == final_) return MONTA_ERR_INVALID;
+    if ((rc = check_ws(ws))) return rc;
+    return launch_regather(g, plan_ptrs(g, ws), stage, final_, slice, static_cast<hipStream_t>(stream));
+}
+
+int monta_dispatch_regather(const monta_cfg *cfg, const void *x, void *stage, void *final_, const void *ws,
+                            void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if ((rc = check_act_ptrs(x, stage))) return rc;
+    if ((rc = check_act_ptrs(stage, final_))) return rc;
+    if (stage == final_) return MONTA_ERR_INVALID;
+    if ((rc = check_ws(ws))) return rc;
+    const PlanPtrs p = plan_ptrs(g, ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int S = g.s.S;
+    const int mode = g_pipeline_mode.load();
+    if (mode == 2) {
+        for (int j = 0; j < S; ++j) {
+            if ((rc = launch_pack(g, p, x, stage, j, st))) return rc;
+            if ((rc = launch_regather(g, p, stage, final_, j, st))) return rc;
+        }
+        return MONTA_OK;
+    }
+    if (mode == 1) {
+        if ((rc = launch_pack(g, p, x, stage, 0, st))) return rc;
+        for (int j = 1; j < S; ++j)
+            if ((rc = launch_pack_regather(g, p, x, stage, final_, j, st))) return rc;
+        return launch_regather(g, p, stage, final_, S - 1, st);
+    }
+    // mode 0: packs on the caller's stream, regathers on the side stream, one event per slice
+    DevState *d = nullptr;
+    if ((rc = dev_state(S, &d))) return rc;
+    for (int j = 0; j < S; ++j) {
+        if ((rc = launch_pack(g, p, x, stage, j, st))) return rc;
+        HIP_TRY(hipEventRecord(d->ev[j], st));
+        HIP_TRY(hipStreamWaitEvent(d->side, d->ev[j], 0));
+        if ((rc = launch_regather(g, p, stage, final_, j, d->side))) return rc;
+    }
+    HIP_TRY(hipEventRecord(d->done, d->side));
+    HIP_TRY(hipStreamWaitEvent(st, d->done, 0));
+    return MONTA_OK;
+}
+
+int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void *out, const void *ws, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (!gates) return MONTA_ERR_NULL;
+    if (misaligned(gates, 4)) return MONTA_ERR_ALIGN;
+    if ((rc = check_act_ptrs(y, out))) return rc;
+    if (y == out) return MONTA_ERR_INVALID;
+    if ((rc = check_ws(ws))) return rc;
+    const Shape &s = g.s;
+    const PlanPtrs p = plan_ptrs(g, ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ProfScope ps(MONTA_K_COMBINE, st);
+    const dim3 grid(mover_grid(s, s.T)), block(kMoverThreads);
+    if (cfg->dtype == MONTA_BF16)
+        hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, st, static_cast<const u32x4 *>(y), gates,
+                           static_cast<u32x4 *>(out), p, s);
+    else
+        hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, st, static_cast<const u32x4 *>(y), gates,
+                           static_cast<u32x4 *>(out), p, s);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+int monta_set_pipeline_mode(int mode)
+{
+    if (mode < 0 || mode > 2) return MONTA_ERR_INVALID;
+    g_pipeline_mode.store(mode);
+    return MONTA_OK;
+}
+
+int monta_get_pipeline_mode(void) { return g_pipeline_mode.load(); }
+
+int monta_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src) return MONTA_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return MONTA_ERR_INVALID;
+    if (misaligned(dst, 16) || misaligned(src, 16)) return MONTA_ERR_ALIGN;
+    const size_t nvec = bytes / 16;
+    size_t wg = (nvec + (size_t)kMoverThreads * kVecInFlight - 1) / ((size_t)kMoverThreads * kVecInFlight);
+    if (wg > (size_t)kMaxMoverGrid) wg = kMaxMoverGrid;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ProfScope ps(MONTA_K_COPY, st);
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)wg), dim3(kMoverThreads), 0, st, static_cast<const u32x4 *>(src),
+                       static_cast<u32x4 *>(dst), nvec);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+int monta_profile_enable(int on)
+{
+    g_prof_on.store(on ? 1 : 0);
+    return MONTA_OK;
+}
+
+int monta_profile_reset(void)
+{
+    int rc = prof_drain();
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (int i = 0; i < MONTA_K_COUNT; ++i) {
+        g_prof_ms[i] = 0.0;
+        g_prof_n[i] = 0;
+    }
+    return rc;
+}
+
+int monta_profile_read(int kernel_id, double *total_ms, int64_t *launches)
+{
+    if (!total_ms || !launches) return MONTA_ERR_NULL;
+    if (kernel_id < 0 || kernel_id >= MONTA_K_COUNT) return MONTA_ERR_INVALID;
+    int rc = prof_drain();
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    *total_ms = g_prof_ms[kernel_id];
+    *launches = g_prof_n[kernel_id];
+    return rc;
+}
+
+const char *monta_strerror(int code)
+{
+    switch (code) {
+        case MONTA_OK: return "ok";
+        case MONTA_ERR_INVALID: return "invalid argument (size, flag or slice violates the preconditions)";
+        case MONTA_ERR_UNSUPPORTED: return "shape outside the library's limits";
+        case MONTA_ERR_NULL: return "required pointer is NULL";
+        case MONTA_ERR_HIP: return "HIP runtime call failed (see monta_last_hip_error)";
+        case MONTA_ERR_ALIGN: return "pointer is not aligned as required";
+        default: return "unknown monta status";
+    }
+}
+
+int monta_last_hip_error(void) { return g_last_hip; }
+
+}  // extern "C"

@@ -1,0 +1,137 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every
+symbol include/monta.h declares, and turns bad arguments into error codes before
+any HIP call (so these run on a machine with no GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2411_00662_amd as m
+from paper_2411_00662_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def good():
+    return m.make_cfg(8192, 4096, m.BF16, 8, 2, 8, 1, 4, 2.0)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "monta.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(monta_[a-z_0-9]+)\s*\(", header))
+    assert declared, "no declarations found in the header"
+    assert declared == set(B.EXPORTS)
+    lib = B.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_sizes_match_the_header_layout():
+    # int64 + 8 * int32 + float + int32 => 48 bytes; layout: 3 * int64 + 4 * int32 + 14 * int64
+    assert ctypes.sizeof(B.monta_cfg) == 48
+    assert ctypes.sizeof(B.monta_ws_layout) == 3 * 8 + 4 * 4 + 14 * 8
+
+
+def test_workspace_query_named_workloads():
+    ws, rows = m.monta_workspace_bytes(good())
+    assert rows == 16384 and ws > 2 * 8192 * 2 * 4
+    L = m.monta_ws_layout_query(m.make_cfg(65536, 7168, m.BF16, 64, 8, 8, 4, 8, 1.25))
+    assert L.max_rows == 524288 and L.capacity == 10240 and L.units == 32 and L.tokens_per_unit == 2048
+    L = m.monta_ws_layout_query(m.make_cfg(256, 128, m.FP32, 4, 2, 2, 2, 2, 0.0))
+    assert L.max_rows == 512 and L.capacity == 256
+    # cf binds the row bound: E*C < T*k
+    L = m.monta_ws_layout_query(m.make_cfg(1024, 64, m.BF16, 4, 2, 2, 1, 1, 0.5))
+    assert L.capacity == 256 and L.max_rows == 1024
+    offs = [getattr(L, f) for f, _ in B.monta_ws_layout._fields_ if f.startswith("off_")]
+    assert offs == sorted(offs) and len(set(offs)) == len(offs) and all(o % 256 == 0 for o in offs)
+    assert L.ws_bytes > offs[-1]
+
+
+@pytest.mark.parametrize("field,value,code", [
+    ("tokens", 0, -1), ("hidden", 0, -1), ("experts", 0, -1), ("top_k", 0, -1), ("ep", 0, -1), ("tp", 0, -1),
+    ("slices", 0, -1), ("dtype", 2, -1), ("renorm", 2, -1),
+    ("top_k", 9, -1),            # k > E
+    ("ep", 3, -1),               # E % ep != 0
+    ("slices", 3, -1),           # T % (S*tp) != 0
+    ("hidden", 4100, -1),        # row bytes not a multiple of 16 (bf16: 8200)
+    ("capacity_factor", -1.0, -1), ("capacity_factor", float("nan"), -1), ("capacity_factor", float("inf"), -1),
+])
+def test_invalid_cfg_is_rejected(field, value, code):
+    cfg = good()
+    setattr(cfg, field, value)
+    with pytest.raises(m.MontaError) as ei:
+        m.monta_workspace_bytes(cfg)
+    assert ei.value.code == code
+
+
+def test_unsupported_limits():
+    with pytest.raises(m.MontaError) as ei:
+        m.monta_workspace_bytes(m.make_cfg(1024, 64, m.BF16, 512, 2, 1, 1, 1, 0.0))
+    assert ei.value.code == -2
+    with pytest.raises(m.MontaError) as ei:
+        m.monta_workspace_bytes(m.make_cfg(1024, 64, m.BF16, 64, 33, 1, 1, 1, 0.0))
+    assert ei.value.code == -2
+    with pytest.raises(m.MontaError) as ei:
+        m.monta_workspace_bytes(m.make_cfg(2 ** 30, 64, m.BF16, 8, 4, 1, 1, 1, 0.0))   # T*k >= 2^31
+    assert ei.value.code == -2
+
+
+def test_null_and_misaligned_pointers_fail_before_any_gpu_work():
+    lib = B.lib()
+    cfg = good()
+    c = ctypes.byref(cfg)
+    fake = 0x1000    # never dereferenced: validation fails first
+    assert lib.monta_route(c, 0, fake, fake, fake, 0) == -3
+    assert lib.monta_route(c, fake, fake, fake, 0, 0) == -3
+    assert lib.monta_route(c, fake + 2, fake, fake, fake, 0) == -5
+    assert lib.monta_dispatch(c, 0, fake, fake, 0, 0) == -3
+    assert lib.monta_dispatch(c, fake, fake + 8, fake, 0, 0) == -5
+    assert lib.monta_dispatch(c, fake, fake, fake, 4, 0) == -1        # slice out of range
+    assert lib.monta_dispatch(c, fake, fake, fake, -2, 0) == -1
+    assert lib.monta_regather(c, fake, fake, fake, 0, 0) == -1        # in place is not allowed
+    assert lib.monta_regather(c, fake, 0, fake, 0, 0) == -3
+    assert lib.monta_regather(c, fake, 2 * fake, fake, 7, 0) == -1
+    assert lib.monta_dispatch_regather(c, fake, 2 * fake, 0, fake, 0) == -3
+    assert lib.monta_dispatch_regather(c, fake, 2 * fake, 2 * fake, fake, 0) == -1
+    assert lib.monta_combine(c, fake, 0, 2 * fake, fake, 0) == -3
+    assert lib.monta_combine(c, fake, fake, fake, fake, 0) == -1
+    assert lib.monta_combine(c, fake, fake, 2 * fake + 4, fake, 0) == -5
+    assert lib.monta_ws_init(c, 0, 0) == -3
+    assert lib.monta_copy(0, fake, 16, 0) == -3
+    assert lib.monta_copy(fake, 2 * fake, 24, 0) == -1
+    assert lib.monta_copy(fake, 2 * fake + 4, 32, 0) == -5
+    assert lib.monta_workspace_bytes(None, None, None) == -3
+    assert lib.monta_ws_layout_query(c, None) == -3
+    assert lib.monta_profile_read(99, ctypes.byref(ctypes.c_double()), ctypes.byref(ctypes.c_int64())) == -1
+    bad = good()
+    bad.top_k = 0
+    assert lib.monta_route(ctypes.byref(bad), fake, fake, fake, fake, 0) == -1
+
+
+def test_pipeline_mode_and_strerror():
+    assert m.monta_get_pipeline_mode() in (0, 1, 2)
+    old = m.monta_get_pipeline_mode()
+    for mode in (0, 1, 2):
+        m.monta_set_pipeline_mode(mode)
+        assert m.monta_get_pipeline_mode() == mode
+    with pytest.raises(m.MontaError):
+        m.monta_set_pipeline_mode(3)
+    m.monta_set_pipeline_mode(old)
+    for code in (0, -1, -2, -3, -4, -5, -77):
+        assert isinstance(m.monta_strerror(code), str) and m.monta_strerror(code)
+    assert m.monta_last_hip_error() == 0
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2411_00662_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2411_00662_amd" not in text and "libmonta.so" not in text

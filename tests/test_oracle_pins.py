@@ -315,13 +315,20 @@ def test_tp_and_slices_do_not_change_the_result():
 
 # ------------------------------------------------------------------ combine
 
-def test_round_trip_top1_is_bit_exact():
+def test_round_trip_top1_is_exact():
     for dtype in (FP32, BF16):
         w = Workload("t", 128, 32, dtype, 4, 1, 2, 2, 2, 0.0)
         logits, x = workloads.make_inputs(w, seed=5)
+        x[3, 7] = 0 if dtype == FP32 else 0x8000          # a negative zero (bf16) / zero
+        if dtype == FP32:
+            x[3, 8] = -0.0
         r = oracle.forward(logits, x, k=1, ep=2, tp=2, S=2, cf=0.0)
         assert (r.gates == 1.0).all()
-        np.testing.assert_array_equal(r.out, x)
+        # exact as values; the sum starts from +0, so 0 + 1*(-0) = +0: a -0 input comes back as +0
+        as_f = (lambda a: a) if dtype == FP32 else workloads.bf16_bits_to_f32
+        np.testing.assert_array_equal(as_f(r.out), as_f(x))
+        nz = as_f(x) != 0
+        np.testing.assert_array_equal(r.out[nz], x[nz])
 
 
 def test_round_trip_topk_renorm_returns_input():
