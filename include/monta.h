@@ -165,16 +165,39 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
 int monta_set_pipeline_mode(int mode);
 int monta_get_pipeline_mode(void);
 
+/* How monta_route builds the plan tables.  -1 (default): when the per-workgroup
+ * histogram table is small (num_blocks * experts <= 65536) every workgroup of the
+ * positions kernel rebuilds the scans it needs from that table (no serial tail);
+ * otherwise, and always with mode 0, the last route workgroup to finish does the
+ * scans once (ticket counter) and a separate kernel finishes the positions.  Both
+ * produce identical tables.  Process-wide. */
+int monta_set_plan_mode(int mode);
+int monta_get_plan_mode(void);
+
+/* Cache policy of the row movers: a bit mask saying which streams use non-temporal
+ * (streaming) accesses: 1 pack loads, 2 pack stores, 4 regather loads, 8 regather
+ * stores, 16 combine loads, 32 combine stores.  A clear bit leaves that stream
+ * cacheable, which pays when the next kernel finds the data in the memory-side cache.
+ * -1 (default) lets the library choose from the working-set size.  Process-wide. */
+int monta_set_cache_policy(int policy);
+int monta_get_cache_policy(void);
+
 /* Plain device copy of `bytes` (multiple of 16, 16-byte aligned pointers) with the
  * same 16-byte-per-lane access pattern as the row movers.  It exists to measure
  * the achievable copy bandwidth and to calibrate profiler byte counters. */
 int monta_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /* Per-kernel timing with HIP events recorded on the launching stream.
- * monta_profile_enable(1) starts bracketing every kernel launch; monta_profile_read
- * synchronises with the recorded events and returns the summed duration and the
- * launch count of one kernel class since the last reset.  Meant for benchmarks:
- * bracketing adds host work per launch. */
+ * After monta_profile_enable(1) every kernel launch is followed by an event; a
+ * kernel's duration runs from the previous such event on its stream (the end of
+ * the kernel before it) to its own, so back-to-back launches are timed without
+ * gaps; a duration includes the kernel's launch latency and the stream time of
+ * one event marker (a few microseconds, which a caller can estimate from the
+ * slow-down of the whole sequence while profiling is on).  Only the library's
+ * own launches are seen: other work put on the stream in between is charged to
+ * the next kernel.  monta_profile_read synchronises with the recorded events and
+ * returns the summed duration and the launch count of one kernel class since the
+ * last reset.  Meant for benchmarks: it adds host work per launch. */
 enum monta_kernel_id {
     MONTA_K_ROUTE = 0,      /* top-k + gates + histogram + scan               */
     MONTA_K_POSITIONS = 1,  /* per-pair positions and row map                 */

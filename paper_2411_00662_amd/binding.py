@@ -48,7 +48,7 @@ class monta_ws_layout(ctypes.Structure):
 # every symbol include/monta.h declares
 EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "monta_route", "monta_dispatch",
            "monta_regather", "monta_dispatch_regather", "monta_combine", "monta_set_pipeline_mode",
-           "monta_get_pipeline_mode", "monta_copy", "monta_profile_enable", "monta_profile_reset",
+           "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
            "monta_profile_read", "monta_strerror", "monta_last_hip_error"]
 
 _lib = None
@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.monta_combine.argtypes = [cfgp, vp, vp, vp, vp, vp]
         L.monta_set_pipeline_mode.argtypes = [i32]
         L.monta_get_pipeline_mode.argtypes = []
+        L.monta_set_cache_policy.argtypes = [i32]
+        L.monta_set_plan_mode.argtypes = [i32]
+        L.monta_get_plan_mode.argtypes = []
+        L.monta_get_cache_policy.argtypes = []
         L.monta_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.monta_profile_enable.argtypes = [i32]
         L.monta_profile_reset.argtypes = []
@@ -199,6 +203,22 @@ def monta_set_pipeline_mode(mode: int):
 
 def monta_get_pipeline_mode() -> int:
     return int(lib().monta_get_pipeline_mode())
+
+
+def monta_set_plan_mode(mode: int):
+    _check(lib().monta_set_plan_mode(int(mode)), "monta_set_plan_mode")
+
+
+def monta_get_plan_mode() -> int:
+    return int(lib().monta_get_plan_mode())
+
+
+def monta_set_cache_policy(policy: int):
+    _check(lib().monta_set_cache_policy(int(policy)), "monta_set_cache_policy")
+
+
+def monta_get_cache_policy() -> int:
+    return int(lib().monta_get_cache_policy())
 
 
 def monta_copy(dst, src, nbytes: int, stream=None):

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstring>
@@ -19,6 +20,8 @@ using namespace monta;
 
 thread_local int g_last_hip = 0;
 std::atomic<int> g_pipeline_mode{1};
+std::atomic<int> g_plan_mode{-1};      // -1: per-workgroup rebuild when the histogram table is small; 0: always ticketed scan
+std::atomic<int> g_cache_policy{-1};   // -1: chosen from the working-set size
 
 #define HIP_TRY(expr)                          \
     do {                                       \
@@ -103,11 +106,23 @@ int validate(const monta_cfg *c, Geometry *g)
     const int64_t nb = (int64_t)s.bpu * U;
     if (nb * s.E > 0x7fffffffLL) return MONTA_ERR_UNSUPPORTED;
     s.num_blocks = (int32_t)nb;
+    // the per-workgroup rebuild of the scans reads num_blocks*E counters in every workgroup
+    s.fast_plan = (g_plan_mode.load() != 0 && nb * s.E <= 65536) ? 1 : 0;
     g->route_lds = route_lds_bytes(TB, s.E, s.k);
     g->route_threads = TB < kWave ? kWave : TB;
     const int64_t tk = c->tokens * (int64_t)c->top_k, ec = (int64_t)c->experts * s.C;
     g->max_rows = tk < ec ? tk : ec;
     s.max_rows = (int32_t)g->max_rows;
+    {
+        // Measured on MI355X (256 MB memory-side cache): a producer's cacheable stores pay when the
+        // consumer kernel reads them back soon; beyond the cache everything but the pack stores streams.
+        const int pol = g_cache_policy.load();
+        const int64_t touched = (2 * c->tokens + 2 * g->max_rows) * row;   // x + out + STAGE + FINAL
+        if (pol >= 0) s.cache = pol;
+        else if (touched <= (384ll << 20)) s.cache = NT_REG_LD | NT_COMB_ST;
+        else if (touched <= (1024ll << 20)) s.cache = NT_REG_LD | NT_REG_ST | NT_COMB_LD | NT_COMB_ST;
+        else s.cache = NT_PACK_LD | NT_REG_LD | NT_REG_ST | NT_COMB_LD | NT_COMB_ST;
+    }
     g->row_bytes = row;
     return MONTA_OK;
 }
@@ -171,6 +186,12 @@ PlanPtrs plan_ptrs(const Geometry &g, const void *ws)
 inline bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 // ------------------------------------------------------------- profiling
+//
+// One event is recorded after every kernel launch, on the launching stream.  A
+// kernel's duration is the time from the previous such event on the same stream
+// (the end of the previous kernel) to its own event, so consecutive kernels are
+// timed back to back without a second marker between them; the first kernel of a
+// chain, or one that follows a cross-stream wait, gets a start event of its own.
 
 struct ProfRec {
     int kid;
@@ -179,29 +200,56 @@ struct ProfRec {
 std::mutex g_prof_mu;
 std::atomic<int> g_prof_on{0};
 std::vector<ProfRec> g_prof_recs;
+std::vector<hipEvent_t> g_prof_events;                        // everything created, destroyed when drained
+std::vector<std::pair<hipStream_t, hipEvent_t>> g_prof_last;  // last end event per stream
 double g_prof_ms[MONTA_K_COUNT] = {0};
 int64_t g_prof_n[MONTA_K_COUNT] = {0};
+
+void prof_break_chain(hipStream_t st)
+{
+    if (!g_prof_on.load()) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (auto &pr : g_prof_last)
+        if (pr.first == st) pr.second = nullptr;
+}
 
 struct ProfScope {
     hipStream_t st;
     int kid;
-    hipEvent_t a = nullptr, b = nullptr;
+    hipEvent_t a = nullptr;
     bool on;
     ProfScope(int kid_, hipStream_t st_) : st(st_), kid(kid_), on(g_prof_on.load() != 0)
     {
         if (!on) return;
-        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
-            on = false;
-            return;
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        for (auto &pr : g_prof_last)
+            if (pr.first == st) a = pr.second;
+        if (!a) {
+            if (hipEventCreate(&a) != hipSuccess) {
+                on = false;
+                a = nullptr;
+                return;
+            }
+            g_prof_events.push_back(a);
+            (void)hipEventRecord(a, st);
         }
-        (void)hipEventRecord(a, st);
     }
     ~ProfScope()
     {
         if (!on) return;
+        hipEvent_t b = nullptr;
+        if (hipEventCreate(&b) != hipSuccess) return;
         (void)hipEventRecord(b, st);
         std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof_events.push_back(b);
         g_prof_recs.push_back({kid, a, b});
+        bool found = false;
+        for (auto &pr : g_prof_last)
+            if (pr.first == st) {
+                pr.second = b;
+                found = true;
+            }
+        if (!found) g_prof_last.push_back({st, b});
     }
 };
 
@@ -220,10 +268,11 @@ int prof_drain()
             g_last_hip = (int)e;
             rc = MONTA_ERR_HIP;
         }
-        (void)hipEventDestroy(r.a);
-        (void)hipEventDestroy(r.b);
     }
+    for (hipEvent_t ev : g_prof_events) (void)hipEventDestroy(ev);
+    g_prof_events.clear();
     g_prof_recs.clear();
+    g_prof_last.clear();
     return rc;
 }
 
@@ -268,6 +317,15 @@ int mover_grid(const Shape &s, int64_t rows)
     return (int)g;
 }
 
+// The row count of a slice is only known on the device; the grid is sized from the host-side bound.
+// With capacity drops most of those workgroups would find nothing to do, and an idle workgroup still
+// costs dispatch time, so the grid stops at 32768 workgroups and the kernel strides over the rest.
+int regather_grid(const Shape &s, int64_t rows_bound)
+{
+    const int g = mover_grid(s, rows_bound);
+    return g < 32768 ? g : 32768;
+}
+
 int64_t slice_rows_bound(const Geometry &g, int nslices_covered)
 {
     int64_t r = (int64_t)g.s.tp * g.s.Tu * nslices_covered * g.s.k;
@@ -294,7 +352,7 @@ int launch_regather(const Geometry &g, const PlanPtrs &p, const void *stage, voi
     const int u1 = slice < 0 ? s.U : (slice + 1) * s.tp;
     const int64_t bound = slice_rows_bound(g, slice < 0 ? s.S : 1);
     ProfScope ps(MONTA_K_REGATHER, st);
-    hipLaunchKernelGGL(regather_kernel, dim3(mover_grid(s, bound)), dim3(kMoverThreads), 0, st,
+    hipLaunchKernelGGL(regather_kernel, dim3(regather_grid(s, bound)), dim3(kMoverThreads), 0, st,
                        static_cast<const u32x4 *>(stage), static_cast<u32x4 *>(fin), p, s, u0, u1);
     HIP_TRY(hipGetLastError());
     return MONTA_OK;
@@ -307,7 +365,7 @@ int launch_pack_regather(const Geometry &g, const PlanPtrs &p, const void *x, vo
     const Shape &s = g.s;
     const int per_slice = s.tp * s.Tu;
     const int n_pack = mover_grid(s, per_slice);
-    const int n_reg = mover_grid(s, slice_rows_bound(g, 1));
+    const int n_reg = regather_grid(s, slice_rows_bound(g, 1));
     ProfScope ps(MONTA_K_PACK_REGATHER, st);
     hipLaunchKernelGGL(pack_regather_kernel, dim3(n_pack + n_reg), dim3(kMoverThreads), 0, st,
                        static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), static_cast<u32x4 *>(fin), p, s,
@@ -388,7 +446,10 @@ int monta_route(const monta_cfg *cfg, const float *logits, int32_t *topk_idx, fl
     }
     {
         ProfScope ps(MONTA_K_POSITIONS, st);
-        hipLaunchKernelGGL(positions_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, topk_idx, p, s);
+        if (s.fast_plan)
+            hipLaunchKernelGGL(plan_positions_kernel, dim3(s.num_blocks), dim3(g.route_threads), 0, st, topk_idx, p, s);
+        else
+            hipLaunchKernelGGL(positions_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, topk_idx, p, s);
         HIP_TRY(hipGetLastError());
     }
     return MONTA_OK;
@@ -451,10 +512,12 @@ int monta_dispatch_regather(const monta_cfg *cfg, const void *x, void *stage, vo
         if ((rc = launch_pack(g, p, x, stage, j, st))) return rc;
         HIP_TRY(hipEventRecord(d->ev[j], st));
         HIP_TRY(hipStreamWaitEvent(d->side, d->ev[j], 0));
+        prof_break_chain(d->side);
         if ((rc = launch_regather(g, p, stage, final_, j, d->side))) return rc;
     }
     HIP_TRY(hipEventRecord(d->done, d->side));
     HIP_TRY(hipStreamWaitEvent(st, d->done, 0));
+    prof_break_chain(st);
     return MONTA_OK;
 }
 
@@ -473,12 +536,16 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
     hipStream_t st = static_cast<hipStream_t>(stream);
     ProfScope ps(MONTA_K_COMBINE, st);
     const dim3 grid(mover_grid(s, s.T)), block(kMoverThreads);
-    if (cfg->dtype == MONTA_BF16)
-        hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, st, static_cast<const u32x4 *>(y), gates,
-                           static_cast<u32x4 *>(out), p, s);
-    else
-        hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, st, static_cast<const u32x4 *>(y), gates,
-                           static_cast<u32x4 *>(out), p, s);
+    const bool wide = s.vpr > 2 * kMoverThreads;     // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
+    const u32x4 *yv = static_cast<const u32x4 *>(y);
+    u32x4 *ov = static_cast<u32x4 *>(out);
+    if (cfg->dtype == MONTA_BF16) {
+        if (wide) hipLaunchKernelGGL((combine_kernel<true, 4>), grid, block, 0, st, yv, gates, ov, p, s);
+        else hipLaunchKernelGGL((combine_kernel<true, 2>), grid, block, 0, st, yv, gates, ov, p, s);
+    } else {
+        if (wide) hipLaunchKernelGGL((combine_kernel<false, 4>), grid, block, 0, st, yv, gates, ov, p, s);
+        else hipLaunchKernelGGL((combine_kernel<false, 2>), grid, block, 0, st, yv, gates, ov, p, s);
+    }
     HIP_TRY(hipGetLastError());
     return MONTA_OK;
 }
@@ -491,6 +558,24 @@ int monta_set_pipeline_mode(int mode)
 }
 
 int monta_get_pipeline_mode(void) { return g_pipeline_mode.load(); }
+
+int monta_set_plan_mode(int mode)
+{
+    if (mode != -1 && mode != 0) return MONTA_ERR_INVALID;
+    g_plan_mode.store(mode);
+    return MONTA_OK;
+}
+
+int monta_get_plan_mode(void) { return g_plan_mode.load(); }
+
+int monta_set_cache_policy(int policy)
+{
+    if (policy < -1 || policy > 63) return MONTA_ERR_INVALID;
+    g_cache_policy.store(policy);
+    return MONTA_OK;
+}
+
+int monta_get_cache_policy(void) { return g_cache_policy.load(); }
 
 int monta_copy(void *dst, const void *src, size_t bytes, void *stream)
 {
@@ -511,6 +596,8 @@ int monta_copy(void *dst, const void *src, size_t bytes, void *stream)
 int monta_profile_enable(int on)
 {
     g_prof_on.store(on ? 1 : 0);
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (auto &pr : g_prof_last) pr.second = nullptr;     // work enqueued while disabled must not be timed
     return MONTA_OK;
 }
 

@@ -9,6 +9,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace monta {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -36,6 +38,14 @@ struct Shape {
     int32_t vpr;       // 16-byte vectors per activation row
     int32_t lpr;       // lanes cooperating on one row in the movers (power of two <= kMoverThreads)
     int32_t max_rows;  // rows STAGE / FINAL hold; every row index read from a table is checked against it
+    int32_t cache;     // CachePolicy bits: which streams of the movers use non-temporal accesses
+    int32_t fast_plan; // 1: plan_positions_kernel rebuilds the scans per workgroup; 0: ticketed scan + positions_kernel
+};
+
+// A set bit makes that stream non-temporal (streaming, no reuse expected); a clear bit leaves
+// it cacheable, which pays when the consumer kernel finds the data still in the memory-side cache.
+enum CachePolicy {
+    NT_PACK_LD = 1, NT_PACK_ST = 2, NT_REG_LD = 4, NT_REG_ST = 8, NT_COMB_LD = 16, NT_COMB_ST = 32
 };
 
 // ------------------------------------------------------------------ helpers
@@ -50,8 +60,32 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
     return v;
 }
 
-__device__ __forceinline__ u32x4 ld16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
-__device__ __forceinline__ void st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(const u32x4 *p)
+{
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
+{
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// Calls f(integral_constant<bool, load_nt>, integral_constant<bool, store_nt>) for the two policy bits:
+// the four variants stay separate loops, so the compiler cannot fold the access kinds together.
+template <typename F>
+__device__ __forceinline__ void with_policy(bool ntl, bool nts, F f)
+{
+    if (ntl) {
+        if (nts) f(std::true_type{}, std::true_type{});
+        else f(std::true_type{}, std::false_type{});
+    } else {
+        if (nts) f(std::false_type{}, std::true_type{});
+        else f(std::false_type{}, std::false_type{});
+    }
+}
 
 // ------------------------------------------------------------ route + plan
 
@@ -64,9 +98,10 @@ __device__ __forceinline__ void st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_
 //  4. every lane ORs its bit into mask[expert][wave] in LDS; popcounts of those
 //     masks give the workgroup's expert histogram and each pair's stable rank inside
 //     the workgroup (lanes hold consecutive tokens, so bit order is token order);
-//  5. the last workgroup to finish (ticket counter) turns the per-workgroup
-//     histograms into every plan table: exclusive scans over workgroups per
-//     expert, capacity clip, expert offsets, per-unit block tables.
+//  5. (only when s.fast_plan == 0) the last workgroup to finish (ticket counter)
+//     turns the per-workgroup histograms into every plan table: exclusive scans
+//     over workgroups per expert, capacity clip, expert offsets, per-unit block
+//     tables.  With s.fast_plan == 1 plan_positions_kernel does that instead.
 // No atomics decide a position: the result is deterministic.
 __global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict__ logits,
                                                          int32_t *__restrict__ topk_idx,
@@ -114,11 +149,19 @@ __global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict
         for (int j = 0; j < k; ++j) {
             int best = -1;
             float bv = 0.f;
-            for (int e = 0; e < E; ++e) {
-                const float v = row[e];
+            auto consider = [&](int e, float v) {
                 const bool after_prev = (v < pv) || (v == pv && e > pi);
                 if (after_prev && (best < 0 || v > bv)) { best = e; bv = v; }
+            };
+            int e = 0;
+            for (; e + 8 <= E; e += 8) {        // eight independent LDS reads in flight per step
+                float v[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) v[q] = row[e + q];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) consider(e + q, v[q]);
             }
+            for (; e < E; ++e) consider(e, row[e]);
             if (best < 0) best = (pi + 1 < E) ? pi + 1 : E - 1;   // unreachable for k <= E; keeps indices in range
             sel[j] = best;
             topk_idx[(size_t)t * k + j] = best;
@@ -126,14 +169,29 @@ __global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict
             pi = best;
             atomicOr(&s_mask[best * NW + wave], 1ull << lane);
         }
+        // gates: w_j = exp(l_j - l_0) in fp64, denominator summed in j (or expert) order, one rounding to fp32.
+        // The first KW weights stay in registers; w_0 = exp(0) = 1 needs no call.
+        constexpr int KW = 8;
         const double top = (double)row[sel[0]];
+        double w[KW];
         double denom = 0.0;
+#pragma unroll
+        for (int j = 0; j < KW; ++j) {
+            w[j] = 0.0;
+            if (j < k) {
+                w[j] = j == 0 ? 1.0 : exp((double)row[sel[j]] - top);
+                if (s.renorm) denom += w[j];
+            }
+        }
         if (s.renorm) {
-            for (int j = 0; j < k; ++j) denom += exp((double)row[sel[j]] - top);
+            for (int j = KW; j < k; ++j) denom += exp((double)row[sel[j]] - top);
         } else {
             for (int e = 0; e < E; ++e) denom += exp((double)row[e] - top);
         }
-        for (int j = 0; j < k; ++j)
+#pragma unroll
+        for (int j = 0; j < KW; ++j)
+            if (j < k) gates[(size_t)t * k + j] = (float)(w[j] / denom);
+        for (int j = KW; j < k; ++j)
             gates[(size_t)t * k + j] = (float)(exp((double)row[sel[j]] - top) / denom);
     }
     __syncthreads();
@@ -153,6 +211,9 @@ __global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict
             p.pos_final[(size_t)t * k + j] = r;     // rank inside the workgroup; finished by positions_kernel
         }
     }
+
+    if (b == 0 && tid == 0) p.meta[META_ALIVE] = 0;   // counted by the kernel that finishes the positions
+    if (s.fast_plan) return;
 
     // ---- ticket: the last workgroup builds the tables
     __threadfence();
@@ -198,7 +259,6 @@ __global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict
             p.offsets[E] = carry;
             p.meta[META_R] = carry;
             p.meta[META_C] = C;
-            p.meta[META_ALIVE] = 0;
         }
     }
     __syncthreads();
@@ -275,6 +335,190 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t *__restric
     if ((threadIdx.x & (kWave - 1)) == 0 && m) atomicAdd(&p.meta[META_ALIVE], __popcll(m));
 }
 
+// Plan + positions in one pass, for problems whose histogram table is small.
+// Workgroup b owns the tokens of route workgroup b.  Every workgroup re-reads the
+// whole [num_blocks][E] histogram table (a few KiB, L2 resident) and reduces it to
+// four per-expert sums: pairs before its unit, pairs in its unit, pairs in its unit
+// before itself, and the total.  Two wave scans over the experts then give the
+// expert offsets and the unit's STAGE block offsets, using the telescoped form
+//   sum_{u' < u} n[u'][e] = min(P[u][e], C),  P[u][e] = pairs of e before unit u,
+// so no table over all units is needed.  The first workgroup of each unit writes
+// that unit's rows of the public tables; workgroup 0 writes the per-expert ones.
+// There is no serial tail and no ticket; the price is the redundant table read.
+__global__ __launch_bounds__(256) void plan_positions_kernel(const int32_t *__restrict__ topk_idx, PlanPtrs p, Shape s)
+{
+    __shared__ int s_before[256], s_unit[256], s_pre[256], s_total[256];
+    __shared__ int s_off[256], s_stage[256];
+    constexpr int PRE = 8;      // pairs per token fetched before the table reduction, to overlap their latency
+    const int E = s.E, k = s.k, C = s.C;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int b = blockIdx.x;
+    const int u = b / s.bpu, ib = b - u * s.bpu;
+    const int t_begin = u * s.Tu + ib * s.TB;
+    int nt = s.Tu - ib * s.TB;
+    if (nt > s.TB) nt = s.TB;
+    const int t = t_begin + tid;
+    const bool active = tid < nt;
+
+    int e_pre[PRE], r_pre[PRE];
+#pragma unroll
+    for (int j = 0; j < PRE; ++j) {
+        e_pre[j] = 0;
+        r_pre[j] = 0;
+        if (active && j < k) {
+            e_pre[j] = topk_idx[(size_t)t * k + j];
+            r_pre[j] = p.pos_final[(size_t)t * k + j];
+        }
+    }
+    for (int e = tid; e < E; e += blockDim.x) s_before[e] = s_unit[e] = s_pre[e] = s_total[e] = 0;
+    __syncthreads();
+
+    // Reduce the histogram table to the four sums per expert.  When the workgroup size is a multiple
+    // of E a lane meets one expert only and sums in registers, with one LDS update at the end.
+    {
+        const int total = s.num_blocks * E;
+        const int first = u * s.bpu, last = first + s.bpu;     // blocks of this unit: [first, last)
+        const int nthr = blockDim.x;
+        if (nthr % E == 0) {
+            // every workgroup reads the same table: each starts at a different chunk and wraps around,
+            // so that at any moment the workgroups pull from different L2 channels
+            const int e = tid % E;
+            int a_total = 0, a_before = 0, a_unit = 0, a_pre = 0;
+            const int bstep = nthr / E;
+            const int nchunks = (total + nthr - 1) / nthr;
+            int c = (int)(((unsigned)b * 7u) % (unsigned)nchunks);
+            for (int n = 0; n < nchunks; ++n) {
+                const int i = c * nthr + tid;
+                if (i < total) {
+                    const int bb = c * bstep + tid / E;
+                    const int cnt = p.block_counts[i];
+                    a_total += cnt;
+                    if (bb < first) a_before += cnt;
+                    else if (bb < last) {
+                        a_unit += cnt;
+                        if (bb < b) a_pre += cnt;
+                    }
+                }
+                if (++c == nchunks) c = 0;
+            }
+            if (a_total) atomicAdd(&s_total[e], a_total);
+            if (a_before) atomicAdd(&s_before[e], a_before);
+            if (a_unit) atomicAdd(&s_unit[e], a_unit);
+            if (a_pre) atomicAdd(&s_pre[e], a_pre);
+        } else {
+            for (int i = tid; i < total; i += nthr) {
+                const int bb = i / E, e = i - bb * E;
+                const int c = p.block_counts[i];
+                if (c == 0) continue;
+                atomicAdd(&s_total[e], c);
+                if (bb < first) atomicAdd(&s_before[e], c);
+                else if (bb < last) {
+                    atomicAdd(&s_unit[e], c);
+                    if (bb < b) atomicAdd(&s_pre[e], c);
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    if (wave == 0) {
+        int carry_off = 0, carry_stage = 0;
+        int base_u = 0;     // sum over experts of min(P[u][e], C): first STAGE row of the unit
+        for (int e0 = 0; e0 < E; e0 += kWave) {
+            const int e = e0 + lane;
+            int v = 0;
+            if (e < E) v = s_before[e] < C ? s_before[e] : C;
+            const int incl = wave_inclusive_scan(v, lane);
+            base_u += __shfl(incl, kWave - 1, kWave);
+        }
+        for (int e0 = 0; e0 < E; e0 += kWave) {
+            const int e = e0 + lane;
+            int kp = 0, nu = 0, cnt = 0, lo = 0;
+            if (e < E) {
+                cnt = s_total[e];
+                kp = cnt < C ? cnt : C;
+                lo = s_before[e] < C ? s_before[e] : C;
+                const int nxt = s_before[e] + s_unit[e];
+                nu = (nxt < C ? nxt : C) - lo;
+            }
+            const int incl_off = wave_inclusive_scan(kp, lane);
+            const int incl_st = wave_inclusive_scan(nu, lane);
+            if (e < E) {
+                const int off = carry_off + incl_off - kp;
+                const int st = base_u + carry_stage + incl_st - nu;
+                s_off[e] = off;
+                s_stage[e] = st;
+                if (ib == 0) {      // first workgroup of the unit publishes the unit's rows
+                    p.n[u * E + e] = nu;
+                    p.stage_off[u * E + e] = st;
+                    p.unit_base[u * E + e] = off + lo;
+                }
+                if (b == 0) {
+                    p.counts[e] = cnt;
+                    p.kept[e] = kp;
+                    p.offsets[e] = off;
+                }
+            }
+            carry_off += __shfl(incl_off, kWave - 1, kWave);
+            carry_stage += __shfl(incl_st, kWave - 1, kWave);
+        }
+        if (lane == 0) {
+            if (ib == 0) p.unit_rows[u] = base_u;
+            if (b == 0) {
+                p.offsets[E] = carry_off;
+                p.unit_rows[s.U] = carry_off;
+                p.meta[META_R] = carry_off;
+                p.meta[META_C] = C;
+            }
+        }
+    }
+    __syncthreads();
+    if (ib == 0) {
+        const int E_loc = E / s.ep;
+        for (int d = tid; d < s.ep; d += blockDim.x) {
+            // rows for EP rank d = STAGE span of its experts inside this unit
+            const int first_e = d * E_loc, end_e = first_e + E_loc;
+            const int begin = s_stage[first_e];
+            int end;
+            if (end_e < E) end = s_stage[end_e];
+            else {
+                const int eL = E - 1;
+                const int lo = s_before[eL] < C ? s_before[eL] : C;
+                const int nxt = s_before[eL] + s_unit[eL];
+                end = s_stage[eL] + ((nxt < C ? nxt : C) - lo);
+            }
+            p.send_rows[u * s.ep + d] = end - begin;
+        }
+    }
+
+    bool any = false;
+    if (active) {
+        auto place = [&](int j, int e, int lr) {
+            const int in_unit = s_pre[e] + lr;          // rank among the unit's pairs of expert e
+            const int r = s_before[e] + in_unit;        // global stable rank
+            int pf = -1, ps = -1;
+            if (r < C) {
+                pf = s_off[e] + r;
+                ps = s_stage[e] + in_unit;
+                if ((unsigned)pf < (unsigned)s.max_rows && (unsigned)ps < (unsigned)s.max_rows) {
+                    p.row_map[ps] = pf;
+                    any = true;
+                } else {
+                    pf = ps = -1;
+                }
+            }
+            p.pos_final[(size_t)t * k + j] = pf;
+            p.pos_stage[(size_t)t * k + j] = ps;
+        };
+#pragma unroll
+        for (int j = 0; j < PRE; ++j)
+            if (j < k) place(j, e_pre[j], r_pre[j]);
+        for (int j = PRE; j < k; ++j) place(j, topk_idx[(size_t)t * k + j], p.pos_final[(size_t)t * k + j]);
+    }
+    const unsigned long long m = __ballot(any);
+    if (lane == 0 && m) atomicAdd(&p.meta[META_ALIVE], __popcll(m));
+}
+
 __global__ void ws_init_kernel(int32_t *meta)
 {
     if (threadIdx.x < META_SLOTS) meta[threadIdx.x] = 0;
@@ -284,7 +528,8 @@ __global__ void ws_init_kernel(int32_t *meta)
 
 // Tokens [t0, t0+nt): each token row is read once and written to the STAGE row of
 // every kept choice (read once / write up to k).  `lpr` lanes share a row.
-__device__ __forceinline__ void pack_rows(const u32x4 *__restrict__ x, u32x4 *__restrict__ stage,
+template <bool NTL, bool NTS>
+__device__ __forceinline__ void pack_rows_t(const u32x4 *__restrict__ x, u32x4 *__restrict__ stage,
                                           const int32_t *__restrict__ pos_stage, const Shape &s, int t0,
                                           int nt, int wg, int nwg)
 {
@@ -294,26 +539,39 @@ __device__ __forceinline__ void pack_rows(const u32x4 *__restrict__ x, u32x4 *__
     for (int i = wg * rows_per_wg + sub; i < nt; i += nwg * rows_per_wg) {
         const int t = t0 + i;
         const int32_t *pos = pos_stage + (size_t)t * k;
+        bool any = false;
+        for (int j = 0; j < k; ++j) any |= (unsigned)pos[j] < (unsigned)s.max_rows;
+        if (!any) continue;                 // every choice of this token was dropped: its row is never read
         const u32x4 *src = x + (size_t)t * vpr;
         for (int v0 = lane; v0 < vpr; v0 += lpr * kVecInFlight) {
             u32x4 val[kVecInFlight];
 #pragma unroll
             for (int q = 0; q < kVecInFlight; ++q)
-                if (v0 + q * lpr < vpr) val[q] = ld16(src + v0 + q * lpr);
+                if (v0 + q * lpr < vpr) val[q] = ld16<NTL>(src + v0 + q * lpr);
             for (int j = 0; j < k; ++j) {
                 const int ps = pos[j];
                 if ((unsigned)ps >= (unsigned)s.max_rows) continue;   // dropped (-1) or not a row
                 u32x4 *dst = stage + (size_t)ps * vpr;
 #pragma unroll
                 for (int q = 0; q < kVecInFlight; ++q)
-                    if (v0 + q * lpr < vpr) st16(dst + v0 + q * lpr, val[q]);
+                    if (v0 + q * lpr < vpr) st16<NTS>(dst + v0 + q * lpr, val[q]);
             }
         }
     }
 }
 
+__device__ __forceinline__ void pack_rows(const u32x4 *__restrict__ x, u32x4 *__restrict__ stage,
+                                          const int32_t *__restrict__ pos_stage, const Shape &s, int t0,
+                                          int nt, int wg, int nwg)
+{
+    with_policy(s.cache & NT_PACK_LD, s.cache & NT_PACK_ST, [&](auto l, auto st) {
+        pack_rows_t<decltype(l)::value, decltype(st)::value>(x, stage, pos_stage, s, t0, nt, wg, nwg);
+    });
+}
+
 // STAGE rows [r0, r1) go to FINAL rows row_map[.]
-__device__ __forceinline__ void regather_rows(const u32x4 *__restrict__ stage, u32x4 *__restrict__ fin,
+template <bool NTL, bool NTS>
+__device__ __forceinline__ void regather_rows_t(const u32x4 *__restrict__ stage, u32x4 *__restrict__ fin,
                                               const int32_t *__restrict__ row_map, const Shape &s, int r0,
                                               int r1, int wg, int nwg)
 {
@@ -331,12 +589,21 @@ __device__ __forceinline__ void regather_rows(const u32x4 *__restrict__ stage, u
             u32x4 val[kVecInFlight];
 #pragma unroll
             for (int q = 0; q < kVecInFlight; ++q)
-                if (v0 + q * lpr < vpr) val[q] = ld16(src + v0 + q * lpr);
+                if (v0 + q * lpr < vpr) val[q] = ld16<NTL>(src + v0 + q * lpr);
 #pragma unroll
             for (int q = 0; q < kVecInFlight; ++q)
-                if (v0 + q * lpr < vpr) st16(dst + v0 + q * lpr, val[q]);
+                if (v0 + q * lpr < vpr) st16<NTS>(dst + v0 + q * lpr, val[q]);
         }
     }
+}
+
+__device__ __forceinline__ void regather_rows(const u32x4 *__restrict__ stage, u32x4 *__restrict__ fin,
+                                              const int32_t *__restrict__ row_map, const Shape &s, int r0,
+                                              int r1, int wg, int nwg)
+{
+    with_policy(s.cache & NT_REG_LD, s.cache & NT_REG_ST, [&](auto l, auto st) {
+        regather_rows_t<decltype(l)::value, decltype(st)::value>(stage, fin, row_map, s, r0, r1, wg, nwg);
+    });
 }
 
 __global__ __launch_bounds__(kMoverThreads) void pack_kernel(const u32x4 *__restrict__ x, u32x4 *__restrict__ stage,
@@ -385,45 +652,43 @@ __global__ __launch_bounds__(kMoverThreads) void pack_regather_kernel(const u32x
 __device__ __forceinline__ double bf16_lo(unsigned int w) { return (double)__uint_as_float(w << 16); }
 __device__ __forceinline__ double bf16_hi(unsigned int w) { return (double)__uint_as_float(w & 0xffff0000u); }
 
-// fp64 -> bf16 bits, one rounding, nearest with ties to even, straight from the
-// fp64 bit pattern (a detour through fp32 would round twice).
+// fp64 -> bf16 bits with ONE rounding (nearest, ties to even).  Going through fp32
+// with two nearest roundings could round twice, so the fp32 step is turned into
+// round-to-odd: truncate toward zero and set the last bit when anything was lost.
+// A round-to-odd value with 16 spare bits rounds to bf16 exactly like the fp64
+// value itself.  Overflow, underflow and infinities fall out of the same path.
 __device__ __forceinline__ unsigned int f64_to_bf16_rne(double d)
 {
-    const unsigned long long u = (unsigned long long)__double_as_longlong(d);
-    const unsigned int sign = (unsigned int)(u >> 48) & 0x8000u;
-    const int ex = (int)((u >> 52) & 0x7ff);
-    const unsigned long long mant = u & 0x000fffffffffffffull;
-    if (ex == 0x7ff) return sign | (mant ? 0x7fc0u : 0x7f80u);
-    const int ef = ex - 1023 + 127;                 // biased exponent of the bf16 / fp32 format
-    if (ef >= 255) return sign | 0x7f80u;
-    if (ef <= 0) {
-        // below the smallest normal: fixed spacing 2^-133; the scaling is exact
-        const double q = __builtin_rint(__builtin_fabs(d) * 0x1p133);
-        return sign | (unsigned int)q;              // q <= 128; 128 is the smallest normal
+    const float f = (float)d;                       // nearest
+    const double back = (double)f;
+    unsigned int u = __float_as_uint(f);
+    if (back != d) {                                // inexact (also true for NaN, handled below)
+        if (__builtin_fabs(back) > __builtin_fabs(d)) u -= 1u;   // step back toward zero: truncation
+        u |= 1u;                                    // sticky bit
     }
-    unsigned int r = ((unsigned int)ef << 7) | (unsigned int)(mant >> 45);
-    const unsigned long long rem = mant & ((1ull << 45) - 1ull), half = 1ull << 44;
-    r += (rem > half || (rem == half && (r & 1u))) ? 1u : 0u;   // a carry walks into the exponent, up to inf
-    return sign | r;
+    const unsigned int r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return d != d ? 0x7fc0u : r;
 }
 
 // out[t] = sum_j gate[t,j] * y[pos_final[t,j]] over kept j in ascending order.
 // The sum is carried in fp64 (every product of an fp32 gate with an fp32 / bf16
 // element is exact there) and rounded once to the activation type, so the rounding
-// decision is taken at the same precision as the CPU reference takes it.  fp64 FMA
-// throughput is far above what the HBM stream of this kernel can feed.
-// A dropped pair is skipped; a token with no kept pair writes zeros.
-template <bool BF16>
-__global__ __launch_bounds__(kMoverThreads) void combine_kernel(const u32x4 *__restrict__ y,
-                                                                const float *__restrict__ gates,
-                                                                u32x4 *__restrict__ out, PlanPtrs p, Shape s)
+// decision is taken at the same precision as the CPU reference takes it; measured
+// against a copy-only version of the same loop the arithmetic costs a few percent.
+// NV 16-byte vectors per lane per pass: 2 covers rows up to 8 KiB in one pass, 4 up
+// to 16 KiB.  Tokens are walked from the last to the first: the FINAL rows written
+// most recently (by the last slices) are read first, while the memory-side cache
+// still holds them.  A dropped pair is skipped; a token with no kept pair writes zeros.
+template <bool BF16, int NV, bool NTL, bool NTS>
+__device__ __forceinline__ void combine_rows_t(const u32x4 *__restrict__ y, const float *__restrict__ gates,
+                                               u32x4 *__restrict__ out, const PlanPtrs &p, const Shape &s)
 {
-    constexpr int NV = 2;                       // 16-byte vectors per lane per pass
     constexpr int NF = BF16 ? 8 : 4;            // accumulators per vector
     const int lpr = s.lpr, vpr = s.vpr, k = s.k;
     const int rows_per_wg = kMoverThreads / lpr;
     const int sub = threadIdx.x / lpr, lane = threadIdx.x - sub * lpr;
-    for (int t = blockIdx.x * rows_per_wg + sub; t < s.T; t += gridDim.x * rows_per_wg) {
+    for (int i = blockIdx.x * rows_per_wg + sub; i < s.T; i += gridDim.x * rows_per_wg) {
+        const int t = s.T - 1 - i;
         const int32_t *pos = p.pos_final + (size_t)t * k;
         const float *g = gates + (size_t)t * k;
         u32x4 *dst = out + (size_t)t * vpr;
@@ -441,7 +706,7 @@ __global__ __launch_bounds__(kMoverThreads) void combine_kernel(const u32x4 *__r
                 u32x4 val[NV];
 #pragma unroll
                 for (int q = 0; q < NV; ++q)
-                    if (v0 + q * lpr < vpr) val[q] = ld16(src + v0 + q * lpr);
+                    if (v0 + q * lpr < vpr) val[q] = ld16<NTL>(src + v0 + q * lpr);
 #pragma unroll
                 for (int q = 0; q < NV; ++q) {
                     if (v0 + q * lpr < vpr) {
@@ -468,11 +733,21 @@ __global__ __launch_bounds__(kMoverThreads) void combine_kernel(const u32x4 *__r
                         else
                             o[c] = __float_as_uint((float)acc[q][c]);
                     }
-                    st16(dst + v0 + q * lpr, o);
+                    st16<NTS>(dst + v0 + q * lpr, o);
                 }
             }
         }
     }
+}
+
+template <bool BF16, int NV>
+__global__ __launch_bounds__(kMoverThreads) void combine_kernel(const u32x4 *__restrict__ y,
+                                                                const float *__restrict__ gates,
+                                                                u32x4 *__restrict__ out, PlanPtrs p, Shape s)
+{
+    with_policy(s.cache & NT_COMB_LD, s.cache & NT_COMB_ST, [&](auto l, auto st) {
+        combine_rows_t<BF16, NV, decltype(l)::value, decltype(st)::value>(y, gates, out, p, s);
+    });
 }
 
 // ------------------------------------------------------------- plain copy
@@ -485,10 +760,10 @@ __global__ __launch_bounds__(kMoverThreads) void copy_kernel(const u32x4 *__rest
         u32x4 val[kVecInFlight];
 #pragma unroll
         for (int q = 0; q < kVecInFlight; ++q)
-            if (base + (size_t)q * kMoverThreads < nvec) val[q] = ld16(src + base + (size_t)q * kMoverThreads);
+            if (base + (size_t)q * kMoverThreads < nvec) val[q] = ld16<true>(src + base + (size_t)q * kMoverThreads);
 #pragma unroll
         for (int q = 0; q < kVecInFlight; ++q)
-            if (base + (size_t)q * kMoverThreads < nvec) st16(dst + base + (size_t)q * kMoverThreads, val[q]);
+            if (base + (size_t)q * kMoverThreads < nvec) st16<true>(dst + base + (size_t)q * kMoverThreads, val[q]);
     }
 }
 

@@ -40,12 +40,14 @@ def cfg_of(m, w: Workload):
     return m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm)
 
 
-def run_gpu(m, w, logits, x, mode=1, how="pipeline", canary=0xA5, repeats=1):
+def run_gpu(m, w, logits, x, mode=1, how="pipeline", canary=0xA5, repeats=1, plan_mode=-1, cache=-1):
     import torch
     from paper_2411_00662_amd import buffers as bufs
     cfg = cfg_of(m, w)
     b = m.alloc_buffers(cfg, logits, x, canary=canary)
     m.monta_set_pipeline_mode(mode)
+    m.monta_set_plan_mode(plan_mode)
+    m.monta_set_cache_policy(cache)
     for _ in range(repeats):
         m.monta_route(cfg, b.logits, b.topk_idx, b.gates, b.ws)
         if how == "pipeline":
@@ -62,6 +64,8 @@ def run_gpu(m, w, logits, x, mode=1, how="pipeline", canary=0xA5, repeats=1):
             raise ValueError(how)
         m.monta_combine(cfg, b.final, b.gates, b.out, b.ws)
     torch.cuda.synchronize()
+    m.monta_set_plan_mode(-1)
+    m.monta_set_cache_policy(-1)
     tabs = m.read_tables(cfg, b.ws)
     res = dict(tabs)
     res["topk_idx"] = b.topk_idx.cpu().numpy()
@@ -138,9 +142,10 @@ def test_tiny_all_modes(m):
     ref = None
     for mode in (0, 1, 2):
         for how in ("pipeline", "all", "slices_reversed"):
-            _say(f"tiny mode={mode} how={how}")
-            got = run_gpu(m, w, logits, x, mode=mode, how=how)
-            ref = check_against_oracle(w, logits, x, got, ref)
+            for plan_mode in (-1, 0):
+                _say(f"tiny mode={mode} how={how} plan_mode={plan_mode}")
+                got = run_gpu(m, w, logits, x, mode=mode, how=how, plan_mode=plan_mode)
+                ref = check_against_oracle(w, logits, x, got, ref)
     # identity experts and renormalised gates: the input comes back
     assert np.all(np.abs(got["out"].astype(np.float64) - x) <= 2 * np.spacing(np.abs(x)))
 
@@ -154,7 +159,11 @@ def test_named_8k_workloads(m, name, seed):
     ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor)
     for mode in ((0, 1, 2) if seed == 0 else (1,)):
         _say(f"{name} seed={seed} mode={mode} gpu")
-        got = run_gpu(m, w, logits, x, mode=mode, repeats=2)
+        got = run_gpu(m, w, logits, x, mode=mode, repeats=2, plan_mode=-1 if mode != 2 else 0)
+        check_against_oracle(w, logits, x, got, ref)
+    for cache in (0, 63, 21, 42):            # every stream cacheable / streaming / mixed
+        _say(f"{name} seed={seed} cache={cache} gpu")
+        got = run_gpu(m, w, logits, x, mode=1, cache=cache)
         check_against_oracle(w, logits, x, got, ref)
     if name == "2x70b":
         # top-1, gate 1.0: exact round trip (as values: 0 + 1*(-0) is +0, so a -0 input comes back as +0)
@@ -204,8 +213,8 @@ def test_skewed_full_size(m):
         got[name] = got[name][:R]
     check_against_oracle(w, logits, x, got, ref, canary=None)
     got.clear()
-    _say("skewed gpu mode 0")
-    got = run_gpu(m, w, logits, x, mode=0)
+    _say("skewed gpu mode 0, ticketed plan")
+    got = run_gpu(m, w, logits, x, mode=0, plan_mode=0)
     for name in ("stage_full", "final_full"):
         got[name] = got[name][:R]
     check_against_oracle(w, logits, x, got, ref, canary=None)
@@ -225,6 +234,8 @@ EDGE = [
     (5120, 2056, BF16, 64, 6, 8, 4, 5, 1.0, 1),     # 257 vectors, Tu = 256
     (2048, 7168, BF16, 32, 8, 8, 4, 4, 0.25, 1),    # 896 vectors: 3.5 passes of 256 lanes
     (600, 64, BF16, 8, 2, 4, 1, 1, 0.01, 1),        # capacity 2: almost everything dropped
+    (4096, 8, BF16, 32, 2, 4, 64, 64, 0.9, 1),      # 4096 one-token units: histogram table too large for the
+                                                    # per-workgroup rebuild, the ticketed scan takes over
 ]
 
 
@@ -235,7 +246,7 @@ def test_edge_shapes(m, T, H, dtype, E, k, ep, tp, S, cf, renorm):
     ref = None
     for mode in (0, 1, 2):
         _say(f"edge {T},{H},{dtype},{E},{k},{ep},{tp},{S},{cf},{renorm} mode={mode}")
-        got = run_gpu(m, w, logits, x, mode=mode)
+        got = run_gpu(m, w, logits, x, mode=mode, plan_mode=-1 if mode != 2 else 0)
         ref = check_against_oracle(w, logits, x, got, ref)
     if cf > 0:
         assert (ref.plan.pos_final < 0).any()
