@@ -61,7 +61,9 @@ def main():
     ap.add_argument("--config", default="mixtral", help="tiny | mixtral | 2x70b | longctx | skewed")
     ap.add_argument("--slices", type=int, default=0, help="override the workload's slice count")
     ap.add_argument("--mode", type=int, default=-1, help="pipeline realisation 0/1/2 (default: library default)")
-    ap.add_argument("--graph", type=int, default=1, help="replay the step from a captured HIP graph (1) or launch eagerly (0)")
+    ap.add_argument("--graph", type=int, default=0, help="replay the step from a captured HIP graph (1) or launch eagerly (0)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run the plain copy kernel on buffers of this size (profiler byte-counter calibration)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     args = ap.parse_args()
@@ -174,13 +176,17 @@ def main():
         movers = [kname for kname in ("pack", "regather", "pack_regather", "combine") if kname in kernels]
         dom = max(movers, key=lambda kname: kernels[kname]["us_per_step"])
         achieved = per_launch[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e9
+        # HBM-side bytes per launch of that kernel from rocprofv3 counters (profiles/traffic.json, written by
+        # `python -m paper_2411_00662_amd.profiling traffic` from two --pmc runs of this same command)
         traffic = None
         tpath = os.path.join(ROOT, "profiles", "traffic.json")
         if os.path.exists(tpath):
             try:
-                tj = json.load(open(tpath))
-                traffic = tj.get(f"{w.name}/S{w.slices}/mode{mode}", {}).get(dom)
-            except (OSError, ValueError):
+                entry = json.load(open(tpath)).get(f"{w.name}/S{w.slices}/mode{mode}", {})
+                for kname, v in entry.items():
+                    if kname.startswith(dom + "_kernel"):
+                        traffic = v["total_bytes"]
+            except (OSError, ValueError, KeyError):
                 traffic = None
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
@@ -191,6 +197,15 @@ def main():
         for v in kernels.values():
             for kk in list(v):
                 v[kk] = round(v[kk], 3)
+
+    if args.calib_copy_mib > 0:
+        nbytes = args.calib_copy_mib << 20
+        src = torch.full((nbytes,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            m.monta_copy(dst, src, nbytes, stream)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- CPU oracle on this host (a baseline for context, never the target)
     cpu = None
