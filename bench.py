@@ -95,8 +95,7 @@ def main():
     stream = torch.cuda.Stream()          # default priority; the whole step is enqueued on it
 
     def step():
-        m.monta_route(cfg, b.logits, b.topk_idx, b.gates, b.ws, stream)
-        m.monta_dispatch_regather(cfg, b.x, b.stage, b.final, b.ws, stream)
+        m.monta_route_dispatch_regather(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, b.ws, stream)
         m.monta_combine(cfg, b.final, b.gates, b.out, b.ws, stream)
 
     torch.cuda.synchronize()
@@ -163,7 +162,8 @@ def main():
                              "us_per_step": avg * n / (prof_steps + 3)}
         m.monta_profile_reset()
         S = w.slices
-        per_launch = {"pack": None, "regather": None, "pack_regather": None, "combine": ab["combine"]}
+        per_launch = {"pack": None, "regather": None, "pack_regather": None, "combine": ab["combine"],
+                      "plan_pack": ab["pack_s"][0] + ab["plan"]}
         if "pack" in kernels:
             npk = round(kernels["pack"]["launches_per_step"])
             per_launch["pack"] = (sum(ab["pack_s"]) if mode != 1 else ab["pack_s"][0]) / npk
@@ -173,7 +173,7 @@ def main():
         if "pack_regather" in kernels:
             tot = sum(ab["pack_s"][j] + ab["regather_s"][j - 1] for j in range(1, S))
             per_launch["pack_regather"] = tot / (S - 1)
-        movers = [kname for kname in ("pack", "regather", "pack_regather", "combine") if kname in kernels]
+        movers = [kname for kname in ("pack", "regather", "pack_regather", "combine", "plan_pack") if kname in kernels]
         dom = max(movers, key=lambda kname: kernels[kname]["us_per_step"])
         achieved = per_launch[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e9
         # HBM-side bytes per launch of that kernel from rocprofv3 counters (profiles/traffic.json, written by

@@ -101,6 +101,7 @@ typedef struct monta_ws_layout {
     int64_t off_row_map;     /* [max_rows] FINAL row of STAGE row s (the per-row index offsets) */
     int64_t off_block_counts;/* [num_blocks][E] internal                                        */
     int64_t off_block_base;  /* [num_blocks][E] internal                                        */
+    int64_t off_local_rank;  /* [T][k] internal: rank of a pair inside its route workgroup      */
 } monta_ws_layout;
 
 /* Host only.  Validates cfg and reports the workspace size and the row capacity
@@ -146,6 +147,14 @@ int monta_regather(const monta_cfg *cfg, const void *stage, void *final_, const 
  * monta_set_pipeline_mode(). */
 int monta_dispatch_regather(const monta_cfg *cfg, const void *x, void *stage, void *final_,
                             const void *ws, void *stream);
+
+/* monta_route followed by monta_dispatch_regather, as one call.  Same results and
+ * same tables.  In pipeline mode 1, for shapes whose histogram table is small, the
+ * kernel that finishes the plan also packs slice 0 (those workgroups derive their
+ * rows themselves), so the first pack does not wait for the plan; otherwise the
+ * call is exactly the two calls in sequence. */
+int monta_route_dispatch_regather(const monta_cfg *cfg, const float *logits, const void *x, int32_t *topk_idx,
+                                  float *gates, void *stage, void *final_, void *ws, void *stream);
 
 /* Unpermutation with scale-add: out[t][:] = sum over kept j (ascending) of
  * gates[t][j] * y[pos_final[t][j]][:], accumulated in fp32 with fused
@@ -206,7 +215,8 @@ enum monta_kernel_id {
     MONTA_K_PACK_REGATHER = 4, /* co-scheduled grid of pipeline mode 1        */
     MONTA_K_COMBINE = 5,
     MONTA_K_COPY = 6,
-    MONTA_K_COUNT = 7
+    MONTA_K_PLAN_PACK = 7,  /* plan + positions + pack of slice 0 in one grid */
+    MONTA_K_COUNT = 8
 };
 int monta_profile_enable(int on);
 int monta_profile_reset(void);

@@ -16,8 +16,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmonta.so")
 
 FP32, BF16 = 0, 1
-K_ROUTE, K_POSITIONS, K_PACK, K_REGATHER, K_PACK_REGATHER, K_COMBINE, K_COPY = range(7)
-KERNEL_NAMES = ["route_plan", "positions", "pack", "regather", "pack_regather", "combine", "copy"]
+K_ROUTE, K_POSITIONS, K_PACK, K_REGATHER, K_PACK_REGATHER, K_COMBINE, K_COPY, K_PLAN_PACK = range(8)
+KERNEL_NAMES = ["route_plan", "positions", "pack", "regather", "pack_regather", "combine", "copy", "plan_pack"]
 
 
 class MontaError(RuntimeError):
@@ -42,12 +42,13 @@ class monta_ws_layout(ctypes.Structure):
                 ("off_unit_base", ctypes.c_int64), ("off_send_rows", ctypes.c_int64),
                 ("off_unit_rows", ctypes.c_int64), ("off_pos_final", ctypes.c_int64),
                 ("off_pos_stage", ctypes.c_int64), ("off_row_map", ctypes.c_int64),
-                ("off_block_counts", ctypes.c_int64), ("off_block_base", ctypes.c_int64)]
+                ("off_block_counts", ctypes.c_int64), ("off_block_base", ctypes.c_int64),
+                ("off_local_rank", ctypes.c_int64)]
 
 
 # every symbol include/monta.h declares
 EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "monta_route", "monta_dispatch",
-           "monta_regather", "monta_dispatch_regather", "monta_combine", "monta_set_pipeline_mode",
+           "monta_regather", "monta_dispatch_regather", "monta_route_dispatch_regather", "monta_combine", "monta_set_pipeline_mode",
            "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
            "monta_profile_read", "monta_strerror", "monta_last_hip_error"]
 
@@ -71,6 +72,7 @@ def lib() -> ctypes.CDLL:
         L.monta_regather.argtypes = [cfgp, vp, vp, vp, i32, vp]
         L.monta_dispatch_regather.argtypes = [cfgp, vp, vp, vp, vp, vp]
         L.monta_combine.argtypes = [cfgp, vp, vp, vp, vp, vp]
+        L.monta_route_dispatch_regather.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.monta_set_pipeline_mode.argtypes = [i32]
         L.monta_get_pipeline_mode.argtypes = []
         L.monta_set_cache_policy.argtypes = [i32]
@@ -187,6 +189,16 @@ def monta_dispatch_regather(cfg, x, stage, final_, ws, stream=None):
     _check(lib().monta_dispatch_regather(ctypes.byref(cfg), _ptr(x, cfg.tokens * row, "x"),
                                          _ptr(stage, L.max_rows * row, "stage"), _ptr(final_, L.max_rows * row, "final_"),
                                          _ptr(ws, L.ws_bytes, "ws"), _stream(stream)), "monta_dispatch_regather")
+
+
+def monta_route_dispatch_regather(cfg, logits, x, topk_idx, gates, stage, final_, ws, stream=None):
+    L = monta_ws_layout_query(cfg)
+    T, E, k = cfg.tokens, cfg.experts, cfg.top_k
+    row = cfg.hidden * _bpe(cfg)
+    _check(lib().monta_route_dispatch_regather(
+        ctypes.byref(cfg), _ptr(logits, T * E * 4, "logits"), _ptr(x, T * row, "x"), _ptr(topk_idx, T * k * 4, "topk_idx"),
+        _ptr(gates, T * k * 4, "gates"), _ptr(stage, L.max_rows * row, "stage"), _ptr(final_, L.max_rows * row, "final_"),
+        _ptr(ws, L.ws_bytes, "ws"), _stream(stream)), "monta_route_dispatch_regather")
 
 
 def monta_combine(cfg, y, gates, out, ws, stream=None):

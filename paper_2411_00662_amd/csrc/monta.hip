@@ -156,6 +156,7 @@ void fill_layout(const Geometry &g, monta_ws_layout *L)
     L->off_row_map = take(g.max_rows);
     L->off_block_counts = take((int64_t)s.num_blocks * s.E);
     L->off_block_base = take((int64_t)s.num_blocks * s.E);
+    L->off_local_rank = take((int64_t)s.T * s.k);
     L->ws_bytes = off;
 }
 
@@ -180,6 +181,7 @@ PlanPtrs plan_ptrs(const Geometry &g, const void *ws)
     p.row_map = at(L.off_row_map);
     p.block_counts = at(L.off_block_counts);
     p.block_base = at(L.off_block_base);
+    p.local_rank = at(L.off_local_rank);
     return p;
 }
 
@@ -381,11 +383,28 @@ int check_act_ptrs(const void *a, const void *b)
     return MONTA_OK;
 }
 
+int launch_route(const Geometry &g, const PlanPtrs &p, const float *logits, int32_t *topk_idx, float *gates,
+                 hipStream_t st)
+{
+    ProfScope ps(MONTA_K_ROUTE, st);
+    hipLaunchKernelGGL(route_plan_kernel, dim3(g.s.num_blocks), dim3(g.route_threads), g.route_lds, st, logits,
+                       topk_idx, gates, p, g.s);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
 int check_ws(const void *ws)
 {
     if (!ws) return MONTA_ERR_NULL;
     if (misaligned(ws, 16)) return MONTA_ERR_ALIGN;
     return MONTA_OK;
+}
+
+int check_route_ptrs(const float *logits, const int32_t *topk_idx, const float *gates, const void *ws)
+{
+    if (!logits || !topk_idx || !gates) return MONTA_ERR_NULL;
+    if (misaligned(logits, 4) || misaligned(topk_idx, 4) || misaligned(gates, 4)) return MONTA_ERR_ALIGN;
+    return check_ws(ws);
 }
 
 }  // namespace
@@ -432,18 +451,11 @@ int monta_route(const monta_cfg *cfg, const float *logits, int32_t *topk_idx, fl
     Geometry g;
     int rc = validate(cfg, &g);
     if (rc) return rc;
-    if (!logits || !topk_idx || !gates) return MONTA_ERR_NULL;
-    if (misaligned(logits, 4) || misaligned(topk_idx, 4) || misaligned(gates, 4)) return MONTA_ERR_ALIGN;
-    if ((rc = check_ws(ws))) return rc;
+    if ((rc = check_route_ptrs(logits, topk_idx, gates, ws))) return rc;
     const Shape &s = g.s;
     PlanPtrs p = plan_ptrs(g, ws);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    {
-        ProfScope ps(MONTA_K_ROUTE, st);
-        hipLaunchKernelGGL(route_plan_kernel, dim3(s.num_blocks), dim3(g.route_threads), g.route_lds, st, logits,
-                           topk_idx, gates, p, s);
-        HIP_TRY(hipGetLastError());
-    }
+    if ((rc = launch_route(g, p, logits, topk_idx, gates, st))) return rc;
     {
         ProfScope ps(MONTA_K_POSITIONS, st);
         if (s.fast_plan)
@@ -453,6 +465,43 @@ int monta_route(const monta_cfg *cfg, const float *logits, int32_t *topk_idx, fl
         HIP_TRY(hipGetLastError());
     }
     return MONTA_OK;
+}
+
+int monta_route_dispatch_regather(const monta_cfg *cfg, const float *logits, const void *x, int32_t *topk_idx,
+                                  float *gates, void *stage, void *final_, void *ws, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if ((rc = check_route_ptrs(logits, topk_idx, gates, ws))) return rc;
+    if ((rc = check_act_ptrs(x, stage))) return rc;
+    if ((rc = check_act_ptrs(stage, final_))) return rc;
+    if (stage == final_) return MONTA_ERR_INVALID;
+    const Shape &s = g.s;
+    const int rows_per_wg = kMoverThreads / s.lpr;
+    // The overlapped form needs a histogram table small enough to rebuild in every pack workgroup and
+    // token groups that never straddle two route workgroups.
+    const bool overlap = g_pipeline_mode.load() == 1 && s.fast_plan && (int64_t)s.num_blocks * s.E <= 2048 &&
+                         s.Tu % s.TB == 0 && rows_per_wg <= s.TB;
+    if (!overlap) {
+        if ((rc = monta_route(cfg, logits, topk_idx, gates, ws, stream))) return rc;
+        return monta_dispatch_regather(cfg, x, stage, final_, ws, stream);
+    }
+    PlanPtrs p = plan_ptrs(g, ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if ((rc = launch_route(g, p, logits, topk_idx, gates, st))) return rc;
+    {
+        const int per_slice = s.tp * s.Tu;
+        const int n_pack = (per_slice + rows_per_wg - 1) / rows_per_wg;     // one token group per workgroup, no striding
+        ProfScope ps(MONTA_K_PLAN_PACK, st);
+        hipLaunchKernelGGL(plan_pack_kernel, dim3(s.num_blocks + n_pack), dim3(kMoverThreads), 0, st, topk_idx,
+                           static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), p, s, 0, per_slice,
+                           s.num_blocks);
+        HIP_TRY(hipGetLastError());
+    }
+    for (int j = 1; j < s.S; ++j)
+        if ((rc = launch_pack_regather(g, p, x, stage, final_, j, st))) return rc;
+    return launch_regather(g, p, stage, final_, s.S - 1, st);
 }
 
 int monta_dispatch(const monta_cfg *cfg, const void *x, void *stage, const void *ws, int slice, void *stream)

@@ -25,7 +25,7 @@ enum { META_R = 0, META_ALIVE = 1, META_C = 2, META_DONE = 3, META_SLOTS = 16 };
 
 struct PlanPtrs {
     int32_t *meta, *counts, *kept, *offsets, *n, *stage_off, *unit_base, *send_rows, *unit_rows;
-    int32_t *pos_final, *pos_stage, *row_map, *block_counts, *block_base;
+    int32_t *pos_final, *pos_stage, *row_map, *block_counts, *block_base, *local_rank;
 };
 
 struct Shape {
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict
             int r = 0;
             for (int w = 0; w < wave; ++w) r += __popcll(s_mask[e * NW + w]);
             r += __popcll(s_mask[e * NW + wave] & below);
-            p.pos_final[(size_t)t * k + j] = r;     // rank inside the workgroup; finished by positions_kernel
+            p.local_rank[(size_t)t * k + j] = r;    // rank inside the workgroup; the positions kernels finish it
         }
     }
 
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t *__restric
         const int32_t *ub = p.block_base + (size_t)u * s.bpu * E;
         for (int j = 0; j < k; ++j) {
             const int e = topk_idx[(size_t)t * k + j];
-            const int r = bb[e] + p.pos_final[(size_t)t * k + j];
+            const int r = bb[e] + p.local_rank[(size_t)t * k + j];
             int pf = -1, ps = -1;
             if (r < s.C) {
                 pf = p.offsets[e] + r;
@@ -335,53 +335,38 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t *__restric
     if ((threadIdx.x & (kWave - 1)) == 0 && m) atomicAdd(&p.meta[META_ALIVE], __popcll(m));
 }
 
-// Plan + positions in one pass, for problems whose histogram table is small.
-// Workgroup b owns the tokens of route workgroup b.  Every workgroup re-reads the
-// whole [num_blocks][E] histogram table (a few KiB, L2 resident) and reduces it to
-// four per-expert sums: pairs before its unit, pairs in its unit, pairs in its unit
-// before itself, and the total.  Two wave scans over the experts then give the
-// expert offsets and the unit's STAGE block offsets, using the telescoped form
+// Shared-memory result of rebuilding the scans for one route workgroup b (see block_plan).
+struct BlockPlan {
+    int before[256];   // P[u][e]: pairs of expert e in units before b's unit
+    int unit[256];     // pairs of e in b's unit
+    int pre[256];      // pairs of e in b's unit, in workgroups before b
+    int total[256];    // counts[e]
+    int off[256];      // offsets[e]: first FINAL row of expert e
+    int stage[256];    // stage_off[u][e]: first STAGE row of block (u, e)
+    int R, unit_row0;
+};
+
+// Every workgroup that calls this re-reads the whole [num_blocks][E] histogram table (a few KiB,
+// L2 resident) and reduces it to four sums per expert; two wave scans over the experts then give
+// the expert offsets and the unit's STAGE block offsets, using the telescoped form
 //   sum_{u' < u} n[u'][e] = min(P[u][e], C),  P[u][e] = pairs of e before unit u,
-// so no table over all units is needed.  The first workgroup of each unit writes
-// that unit's rows of the public tables; workgroup 0 writes the per-expert ones.
-// There is no serial tail and no ticket; the price is the redundant table read.
-__global__ __launch_bounds__(256) void plan_positions_kernel(const int32_t *__restrict__ topk_idx, PlanPtrs p, Shape s)
+// so no table over all units is needed.  There is no serial tail and no ticket; the price is the
+// redundant table read.  All threads of the workgroup must call it; it ends with a barrier.
+__device__ __forceinline__ void block_plan(BlockPlan &bp, int b, const PlanPtrs &p, const Shape &s)
 {
-    __shared__ int s_before[256], s_unit[256], s_pre[256], s_total[256];
-    __shared__ int s_off[256], s_stage[256];
-    constexpr int PRE = 8;      // pairs per token fetched before the table reduction, to overlap their latency
-    const int E = s.E, k = s.k, C = s.C;
+    const int E = s.E, C = s.C;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-    const int b = blockIdx.x;
-    const int u = b / s.bpu, ib = b - u * s.bpu;
-    const int t_begin = u * s.Tu + ib * s.TB;
-    int nt = s.Tu - ib * s.TB;
-    if (nt > s.TB) nt = s.TB;
-    const int t = t_begin + tid;
-    const bool active = tid < nt;
-
-    int e_pre[PRE], r_pre[PRE];
-#pragma unroll
-    for (int j = 0; j < PRE; ++j) {
-        e_pre[j] = 0;
-        r_pre[j] = 0;
-        if (active && j < k) {
-            e_pre[j] = topk_idx[(size_t)t * k + j];
-            r_pre[j] = p.pos_final[(size_t)t * k + j];
-        }
-    }
-    for (int e = tid; e < E; e += blockDim.x) s_before[e] = s_unit[e] = s_pre[e] = s_total[e] = 0;
+    const int u = b / s.bpu;
+    for (int e = tid; e < E; e += blockDim.x) bp.before[e] = bp.unit[e] = bp.pre[e] = bp.total[e] = 0;
     __syncthreads();
-
-    // Reduce the histogram table to the four sums per expert.  When the workgroup size is a multiple
-    // of E a lane meets one expert only and sums in registers, with one LDS update at the end.
     {
         const int total = s.num_blocks * E;
         const int first = u * s.bpu, last = first + s.bpu;     // blocks of this unit: [first, last)
         const int nthr = blockDim.x;
         if (nthr % E == 0) {
-            // every workgroup reads the same table: each starts at a different chunk and wraps around,
-            // so that at any moment the workgroups pull from different L2 channels
+            // A lane meets one expert only and sums in registers, with one LDS update at the end.
+            // Every workgroup reads the same table: each starts at a different chunk and wraps around,
+            // so that at any moment the workgroups pull from different L2 channels.
             const int e = tid % E;
             int a_total = 0, a_before = 0, a_unit = 0, a_pre = 0;
             const int bstep = nthr / E;
@@ -401,91 +386,142 @@ __global__ __launch_bounds__(256) void plan_positions_kernel(const int32_t *__re
                 }
                 if (++c == nchunks) c = 0;
             }
-            if (a_total) atomicAdd(&s_total[e], a_total);
-            if (a_before) atomicAdd(&s_before[e], a_before);
-            if (a_unit) atomicAdd(&s_unit[e], a_unit);
-            if (a_pre) atomicAdd(&s_pre[e], a_pre);
+            if (a_total) atomicAdd(&bp.total[e], a_total);
+            if (a_before) atomicAdd(&bp.before[e], a_before);
+            if (a_unit) atomicAdd(&bp.unit[e], a_unit);
+            if (a_pre) atomicAdd(&bp.pre[e], a_pre);
         } else {
             for (int i = tid; i < total; i += nthr) {
                 const int bb = i / E, e = i - bb * E;
                 const int c = p.block_counts[i];
                 if (c == 0) continue;
-                atomicAdd(&s_total[e], c);
-                if (bb < first) atomicAdd(&s_before[e], c);
+                atomicAdd(&bp.total[e], c);
+                if (bb < first) atomicAdd(&bp.before[e], c);
                 else if (bb < last) {
-                    atomicAdd(&s_unit[e], c);
-                    if (bb < b) atomicAdd(&s_pre[e], c);
+                    atomicAdd(&bp.unit[e], c);
+                    if (bb < b) atomicAdd(&bp.pre[e], c);
                 }
             }
         }
     }
     __syncthreads();
-
     if (wave == 0) {
         int carry_off = 0, carry_stage = 0;
         int base_u = 0;     // sum over experts of min(P[u][e], C): first STAGE row of the unit
         for (int e0 = 0; e0 < E; e0 += kWave) {
             const int e = e0 + lane;
             int v = 0;
-            if (e < E) v = s_before[e] < C ? s_before[e] : C;
+            if (e < E) v = bp.before[e] < C ? bp.before[e] : C;
             const int incl = wave_inclusive_scan(v, lane);
             base_u += __shfl(incl, kWave - 1, kWave);
         }
         for (int e0 = 0; e0 < E; e0 += kWave) {
             const int e = e0 + lane;
-            int kp = 0, nu = 0, cnt = 0, lo = 0;
+            int kp = 0, nu = 0;
             if (e < E) {
-                cnt = s_total[e];
+                const int cnt = bp.total[e];
                 kp = cnt < C ? cnt : C;
-                lo = s_before[e] < C ? s_before[e] : C;
-                const int nxt = s_before[e] + s_unit[e];
+                const int lo = bp.before[e] < C ? bp.before[e] : C;
+                const int nxt = bp.before[e] + bp.unit[e];
                 nu = (nxt < C ? nxt : C) - lo;
             }
             const int incl_off = wave_inclusive_scan(kp, lane);
             const int incl_st = wave_inclusive_scan(nu, lane);
             if (e < E) {
-                const int off = carry_off + incl_off - kp;
-                const int st = base_u + carry_stage + incl_st - nu;
-                s_off[e] = off;
-                s_stage[e] = st;
-                if (ib == 0) {      // first workgroup of the unit publishes the unit's rows
-                    p.n[u * E + e] = nu;
-                    p.stage_off[u * E + e] = st;
-                    p.unit_base[u * E + e] = off + lo;
-                }
-                if (b == 0) {
-                    p.counts[e] = cnt;
-                    p.kept[e] = kp;
-                    p.offsets[e] = off;
-                }
+                bp.off[e] = carry_off + incl_off - kp;
+                bp.stage[e] = base_u + carry_stage + incl_st - nu;
             }
             carry_off += __shfl(incl_off, kWave - 1, kWave);
             carry_stage += __shfl(incl_st, kWave - 1, kWave);
         }
         if (lane == 0) {
-            if (ib == 0) p.unit_rows[u] = base_u;
-            if (b == 0) {
-                p.offsets[E] = carry_off;
-                p.unit_rows[s.U] = carry_off;
-                p.meta[META_R] = carry_off;
-                p.meta[META_C] = C;
-            }
+            bp.R = carry_off;
+            bp.unit_row0 = base_u;
         }
     }
     __syncthreads();
+}
+
+// STAGE and FINAL rows of one pair from the rebuilt scans; false if the pair is dropped.
+__device__ __forceinline__ bool place_pair(const BlockPlan &bp, const Shape &s, int e, int local_rank, int &pf, int &ps)
+{
+    const int in_unit = bp.pre[e] + local_rank;     // rank among the unit's pairs of expert e
+    const int r = bp.before[e] + in_unit;           // global stable rank
+    pf = ps = -1;
+    if (r >= s.C) return false;
+    pf = bp.off[e] + r;
+    ps = bp.stage[e] + in_unit;
+    // always true for a consistent histogram table; guards a workspace that was never initialised
+    if ((unsigned)pf < (unsigned)s.max_rows && (unsigned)ps < (unsigned)s.max_rows) return true;
+    pf = ps = -1;
+    return false;
+}
+
+// Plan + positions in one pass, for problems whose histogram table is small: workgroup b owns the
+// tokens of route workgroup b, rebuilds the scans (block_plan) and writes its tokens' positions.
+// The first workgroup of each unit writes that unit's rows of the public tables; workgroup 0
+// writes the per-expert ones.
+__device__ __forceinline__ void plan_positions_block(BlockPlan &bp, int b, const int32_t *__restrict__ topk_idx,
+                                                     const PlanPtrs &p, const Shape &s)
+{
+    constexpr int PRE = 8;      // pairs per token fetched before the table reduction, to overlap their latency
+    const int E = s.E, k = s.k, C = s.C;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int u = b / s.bpu, ib = b - u * s.bpu;
+    const int t_begin = u * s.Tu + ib * s.TB;
+    int nt = s.Tu - ib * s.TB;
+    if (nt > s.TB) nt = s.TB;
+    const int t = t_begin + tid;
+    const bool active = tid < nt;
+
+    int e_pre[PRE], r_pre[PRE];
+#pragma unroll
+    for (int j = 0; j < PRE; ++j) {
+        e_pre[j] = 0;
+        r_pre[j] = 0;
+        if (active && j < k) {
+            e_pre[j] = topk_idx[(size_t)t * k + j];
+            r_pre[j] = p.local_rank[(size_t)t * k + j];
+        }
+    }
+    block_plan(bp, b, p, s);
+
+    for (int e = tid; e < E; e += blockDim.x) {
+        if (ib == 0) {      // first workgroup of the unit publishes the unit's rows
+            const int lo = bp.before[e] < C ? bp.before[e] : C;
+            const int nxt = bp.before[e] + bp.unit[e];
+            p.n[u * E + e] = (nxt < C ? nxt : C) - lo;
+            p.stage_off[u * E + e] = bp.stage[e];
+            p.unit_base[u * E + e] = bp.off[e] + lo;
+        }
+        if (b == 0) {
+            p.counts[e] = bp.total[e];
+            p.kept[e] = bp.total[e] < C ? bp.total[e] : C;
+            p.offsets[e] = bp.off[e];
+        }
+    }
+    if (tid == 0) {
+        if (ib == 0) p.unit_rows[u] = bp.unit_row0;
+        if (b == 0) {
+            p.offsets[E] = bp.R;
+            p.unit_rows[s.U] = bp.R;
+            p.meta[META_R] = bp.R;
+            p.meta[META_C] = C;
+        }
+    }
     if (ib == 0) {
         const int E_loc = E / s.ep;
         for (int d = tid; d < s.ep; d += blockDim.x) {
             // rows for EP rank d = STAGE span of its experts inside this unit
             const int first_e = d * E_loc, end_e = first_e + E_loc;
-            const int begin = s_stage[first_e];
+            const int begin = bp.stage[first_e];
             int end;
-            if (end_e < E) end = s_stage[end_e];
+            if (end_e < E) end = bp.stage[end_e];
             else {
                 const int eL = E - 1;
-                const int lo = s_before[eL] < C ? s_before[eL] : C;
-                const int nxt = s_before[eL] + s_unit[eL];
-                end = s_stage[eL] + ((nxt < C ? nxt : C) - lo);
+                const int lo = bp.before[eL] < C ? bp.before[eL] : C;
+                const int nxt = bp.before[eL] + bp.unit[eL];
+                end = bp.stage[eL] + ((nxt < C ? nxt : C) - lo);
             }
             p.send_rows[u * s.ep + d] = end - begin;
         }
@@ -494,18 +530,10 @@ __global__ __launch_bounds__(256) void plan_positions_kernel(const int32_t *__re
     bool any = false;
     if (active) {
         auto place = [&](int j, int e, int lr) {
-            const int in_unit = s_pre[e] + lr;          // rank among the unit's pairs of expert e
-            const int r = s_before[e] + in_unit;        // global stable rank
-            int pf = -1, ps = -1;
-            if (r < C) {
-                pf = s_off[e] + r;
-                ps = s_stage[e] + in_unit;
-                if ((unsigned)pf < (unsigned)s.max_rows && (unsigned)ps < (unsigned)s.max_rows) {
-                    p.row_map[ps] = pf;
-                    any = true;
-                } else {
-                    pf = ps = -1;
-                }
+            int pf, ps;
+            if (place_pair(bp, s, e, lr, pf, ps)) {
+                p.row_map[ps] = pf;
+                any = true;
             }
             p.pos_final[(size_t)t * k + j] = pf;
             p.pos_stage[(size_t)t * k + j] = ps;
@@ -513,10 +541,16 @@ __global__ __launch_bounds__(256) void plan_positions_kernel(const int32_t *__re
 #pragma unroll
         for (int j = 0; j < PRE; ++j)
             if (j < k) place(j, e_pre[j], r_pre[j]);
-        for (int j = PRE; j < k; ++j) place(j, topk_idx[(size_t)t * k + j], p.pos_final[(size_t)t * k + j]);
+        for (int j = PRE; j < k; ++j) place(j, topk_idx[(size_t)t * k + j], p.local_rank[(size_t)t * k + j]);
     }
     const unsigned long long m = __ballot(any);
     if (lane == 0 && m) atomicAdd(&p.meta[META_ALIVE], __popcll(m));
+}
+
+__global__ __launch_bounds__(256) void plan_positions_kernel(const int32_t *__restrict__ topk_idx, PlanPtrs p, Shape s)
+{
+    __shared__ BlockPlan bp;
+    plan_positions_block(bp, blockIdx.x, topk_idx, p, s);
 }
 
 __global__ void ws_init_kernel(int32_t *meta)
@@ -603,6 +637,68 @@ __device__ __forceinline__ void regather_rows(const u32x4 *__restrict__ stage, u
 {
     with_policy(s.cache & NT_REG_LD, s.cache & NT_REG_ST, [&](auto l, auto st) {
         regather_rows_t<decltype(l)::value, decltype(st)::value>(stage, fin, row_map, s, r0, r1, wg, nwg);
+    });
+}
+
+// pack for tokens whose positions have not been written yet: the workgroup rebuilds the scans of
+// the route workgroup its tokens belong to (all of them belong to one: the host checks the shape)
+// and derives the STAGE rows itself.  The first pass of every row is loaded before the rebuild, so
+// the table read overlaps the row read.  Writes no table: plan_positions_block does that.
+template <bool NTL, bool NTS>
+__device__ __forceinline__ void pack_rows_selfplan_t(BlockPlan &bp, const u32x4 *__restrict__ x,
+                                                     u32x4 *__restrict__ stage, const int32_t *__restrict__ topk_idx,
+                                                     const PlanPtrs &p, const Shape &s, int t0, int nt, int wg)
+{
+    const int lpr = s.lpr, vpr = s.vpr, k = s.k;
+    const int rows_per_wg = kMoverThreads / lpr;
+    const int sub = threadIdx.x / lpr, lane = threadIdx.x - sub * lpr;
+    const int i = wg * rows_per_wg + sub;
+    const bool have = i < nt;
+    const int t = t0 + (have ? i : 0);
+    const int t_first = t0 + wg * rows_per_wg;                  // same route workgroup for the whole group
+    const int u = t_first / s.Tu;
+    const int b = u * s.bpu + (t_first - u * s.Tu) / s.TB;
+    const u32x4 *src = x + (size_t)t * vpr;
+    u32x4 val[kVecInFlight];
+#pragma unroll
+    for (int q = 0; q < kVecInFlight; ++q)
+        if (have && lane + q * lpr < vpr) val[q] = ld16<NTL>(src + lane + q * lpr);
+    block_plan(bp, b, p, s);
+    if (!have) return;
+    for (int v0 = lane; v0 < vpr; v0 += lpr * kVecInFlight) {
+        if (v0 != lane) {
+#pragma unroll
+            for (int q = 0; q < kVecInFlight; ++q)
+                if (v0 + q * lpr < vpr) val[q] = ld16<NTL>(src + v0 + q * lpr);
+        }
+        for (int j = 0; j < k; ++j) {
+            int pf, ps;
+            if (!place_pair(bp, s, topk_idx[(size_t)t * k + j], p.local_rank[(size_t)t * k + j], pf, ps)) continue;
+            u32x4 *dst = stage + (size_t)ps * vpr;
+#pragma unroll
+            for (int q = 0; q < kVecInFlight; ++q)
+                if (v0 + q * lpr < vpr) st16<NTS>(dst + v0 + q * lpr, val[q]);
+        }
+    }
+}
+
+// One grid, two jobs: the first n_plan workgroups finish the plan (tables and positions of every
+// token), the others pack slice 0 with positions they derive themselves, so the first pack does
+// not wait for the plan kernel.
+__global__ __launch_bounds__(kMoverThreads) void plan_pack_kernel(const int32_t *__restrict__ topk_idx,
+                                                                  const u32x4 *__restrict__ x,
+                                                                  u32x4 *__restrict__ stage, PlanPtrs p, Shape s,
+                                                                  int t0, int nt, int n_plan)
+{
+    __shared__ BlockPlan bp;
+    const int bid = blockIdx.x;
+    if (bid < n_plan) {
+        plan_positions_block(bp, bid, topk_idx, p, s);
+        return;
+    }
+    with_policy(s.cache & NT_PACK_LD, s.cache & NT_PACK_ST, [&](auto l, auto st) {
+        pack_rows_selfplan_t<decltype(l)::value, decltype(st)::value>(bp, x, stage, topk_idx, p, s, t0, nt,
+                                                                      bid - n_plan);
     });
 }
 

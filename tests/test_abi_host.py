@@ -29,9 +29,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_the_header_layout():
-    # int64 + 8 * int32 + float + int32 => 48 bytes; layout: 3 * int64 + 4 * int32 + 14 * int64
+    # int64 + 8 * int32 + float + int32 => 48 bytes; layout: 3 * int64 + 4 * int32 + 15 * int64
     assert ctypes.sizeof(B.monta_cfg) == 48
-    assert ctypes.sizeof(B.monta_ws_layout) == 3 * 8 + 4 * 4 + 14 * 8
+    assert ctypes.sizeof(B.monta_ws_layout) == 3 * 8 + 4 * 4 + 15 * 8
 
 
 def test_workspace_query_named_workloads():
@@ -95,6 +95,9 @@ def test_null_and_misaligned_pointers_fail_before_any_gpu_work():
     assert lib.monta_regather(c, fake, 2 * fake, fake, 7, 0) == -1
     assert lib.monta_dispatch_regather(c, fake, 2 * fake, 0, fake, 0) == -3
     assert lib.monta_dispatch_regather(c, fake, 2 * fake, 2 * fake, fake, 0) == -1
+    assert lib.monta_route_dispatch_regather(c, fake, fake, fake, fake, 2 * fake, 3 * fake, 0, 0) == -3
+    assert lib.monta_route_dispatch_regather(c, fake, fake, fake, fake, 2 * fake, 2 * fake, fake, 0) == -1
+    assert lib.monta_route_dispatch_regather(c, fake, 0, fake, fake, 2 * fake, 3 * fake, fake, 0) == -3
     assert lib.monta_combine(c, fake, 0, 2 * fake, fake, 0) == -3
     assert lib.monta_combine(c, fake, fake, fake, fake, 0) == -1
     assert lib.monta_combine(c, fake, fake, 2 * fake + 4, fake, 0) == -5

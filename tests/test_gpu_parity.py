@@ -49,6 +49,10 @@ def run_gpu(m, w, logits, x, mode=1, how="pipeline", canary=0xA5, repeats=1, pla
     m.monta_set_plan_mode(plan_mode)
     m.monta_set_cache_policy(cache)
     for _ in range(repeats):
+        if how == "fused_call":
+            m.monta_route_dispatch_regather(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, b.ws)
+            m.monta_combine(cfg, b.final, b.gates, b.out, b.ws)
+            continue
         m.monta_route(cfg, b.logits, b.topk_idx, b.gates, b.ws)
         if how == "pipeline":
             m.monta_dispatch_regather(cfg, b.x, b.stage, b.final, b.ws)
@@ -141,7 +145,7 @@ def test_tiny_all_modes(m):
     logits, x = workloads.make_inputs(w)
     ref = None
     for mode in (0, 1, 2):
-        for how in ("pipeline", "all", "slices_reversed"):
+        for how in ("pipeline", "all", "slices_reversed", "fused_call"):
             for plan_mode in (-1, 0):
                 _say(f"tiny mode={mode} how={how} plan_mode={plan_mode}")
                 got = run_gpu(m, w, logits, x, mode=mode, how=how, plan_mode=plan_mode)
@@ -163,8 +167,11 @@ def test_named_8k_workloads(m, name, seed):
         check_against_oracle(w, logits, x, got, ref)
     for cache in (0, 63, 21, 42):            # every stream cacheable / streaming / mixed
         _say(f"{name} seed={seed} cache={cache} gpu")
-        got = run_gpu(m, w, logits, x, mode=1, cache=cache)
+        got = run_gpu(m, w, logits, x, mode=1, cache=cache, how="fused_call" if cache in (0, 21) else "pipeline")
         check_against_oracle(w, logits, x, got, ref)
+    _say(f"{name} seed={seed} fused call, twice")
+    got = run_gpu(m, w, logits, x, mode=1, how="fused_call", repeats=2)
+    check_against_oracle(w, logits, x, got, ref)
     if name == "2x70b":
         # top-1, gate 1.0: exact round trip (as values: 0 + 1*(-0) is +0, so a -0 input comes back as +0)
         np.testing.assert_array_equal(workloads.bf16_bits_to_f32(got["out"]), workloads.bf16_bits_to_f32(x))
@@ -190,7 +197,7 @@ def test_longctx_slice_sweep(m):
             np.testing.assert_array_equal(pl.pos_final, ref1.plan.pos_final)
         for mode in ((0, 1) if S in (1, 4) else (1,)):
             _say(f"longctx S={S} mode={mode} gpu")
-            got = run_gpu(m, w, logits, x, mode=mode)
+            got = run_gpu(m, w, logits, x, mode=mode, how="fused_call" if mode == 1 else "pipeline")
             check_against_oracle(w, logits, x, got, ref)
         del stage
 
@@ -248,6 +255,9 @@ def test_edge_shapes(m, T, H, dtype, E, k, ep, tp, S, cf, renorm):
         _say(f"edge {T},{H},{dtype},{E},{k},{ep},{tp},{S},{cf},{renorm} mode={mode}")
         got = run_gpu(m, w, logits, x, mode=mode, plan_mode=-1 if mode != 2 else 0)
         ref = check_against_oracle(w, logits, x, got, ref)
+    _say(f"edge {T},{H},{dtype},{E},{k},{ep},{tp},{S},{cf},{renorm} fused call")
+    got = run_gpu(m, w, logits, x, mode=1, how="fused_call")
+    check_against_oracle(w, logits, x, got, ref)
     if cf > 0:
         assert (ref.plan.pos_final < 0).any()
 
