@@ -96,7 +96,12 @@ int validate(const monta_cfg *c, Geometry *g)
     s.C = (int32_t)capacity_of(c);
     s.renorm = c->renorm;
     s.vpr = (int32_t)(row / 16);
-    s.lpr = pow2ceil(s.vpr) < kMoverThreads ? pow2ceil(s.vpr) : kMoverThreads;
+#ifdef MONTA_LPR_MAX
+    const int lpr_max = MONTA_LPR_MAX;
+#else
+    const int lpr_max = kMoverThreads;
+#endif
+    s.lpr = pow2ceil(s.vpr) < lpr_max ? pow2ceil(s.vpr) : lpr_max;
     // route workgroup: as many tokens as fit 60 KiB of LDS, at most 256, no more than a unit needs
     int TB = 256;
     while (TB > 32 && (route_lds_bytes(TB, s.E, s.k) > 60 * 1024 || TB / 2 >= s.Tu)) TB >>= 1;
@@ -482,7 +487,7 @@ int monta_route_dispatch_regather(const monta_cfg *cfg, const float *logits, con
     // The overlapped form needs a histogram table small enough to rebuild in every pack workgroup and
     // token groups that never straddle two route workgroups.
     const bool overlap = g_pipeline_mode.load() == 1 && s.fast_plan && (int64_t)s.num_blocks * s.E <= 2048 &&
-                         s.Tu % s.TB == 0 && rows_per_wg <= s.TB;
+                         s.Tu % s.TB == 0 && rows_per_wg <= s.TB && kMoverThreads >= s.TB;
     if (!overlap) {
         if ((rc = monta_route(cfg, logits, topk_idx, gates, ws, stream))) return rc;
         return monta_dispatch_regather(cfg, x, stage, final_, ws, stream);

@@ -17,8 +17,14 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
-constexpr int kMoverThreads = 256;   // threads per workgroup of the row movers
-constexpr int kVecInFlight = 4;      // 16-byte loads issued by a lane before its first store
+#ifndef MONTA_MOVER_THREADS
+#define MONTA_MOVER_THREADS 256
+#endif
+#ifndef MONTA_VEC_IN_FLIGHT
+#define MONTA_VEC_IN_FLIGHT 4
+#endif
+constexpr int kMoverThreads = MONTA_MOVER_THREADS;   // threads per workgroup of the row movers
+constexpr int kVecInFlight = MONTA_VEC_IN_FLIGHT;    // 16-byte loads issued by a lane before its first store
 
 // meta[] slots (int32)
 enum { META_R = 0, META_ALIVE = 1, META_C = 2, META_DONE = 3, META_SLOTS = 16 };
