@@ -222,6 +222,43 @@ int monta_profile_enable(int on);
 int monta_profile_reset(void);
 int monta_profile_read(int kernel_id, double *total_ms, int64_t *launches);
 
+/* ---- planner: the paper's traffic-aware strategy choice (section "Network-traffic-aware") ----
+ * Host only, no GPU work.  Per-chunk times AA_j, AG_j, D2D_j (Eq. 8-10), the O1 cost (Eq. 11),
+ * the chunk-count searches (Algorithm 1 for O2, Algorithm 2 for O3) and the selection of the
+ * cheapest strategy (Algorithm 3).  Where the printed algorithms are garbled the search keeps
+ * the best (N, T) seen while N = 1, 2, ... runs until a chunk falls under i_minimal or n_max.
+ * An efficiency curve is `n` points (volume in bytes ascending, efficiency in (0,1]),
+ * interpolated linearly in the volume and held constant outside the sampled range. */
+typedef struct monta_curve {
+    const double *volume;   /* host pointer, n ascending volumes in bytes  */
+    const double *eff;      /* host pointer, n efficiencies                */
+    int32_t n;              /* >= 1                                        */
+} monta_curve;
+
+typedef struct monta_plan_in {
+    double traffic;         /* I = b*s*h*BPE in bytes (Eq. 3)                                  */
+    int32_t t, e;           /* tensor-parallel and expert-parallel degrees                     */
+    double b1, b2, b3;      /* theoretical AllToAll, AllGather and memory bandwidth, bytes/s   */
+    monta_curve r1, r2, r3; /* efficiency of AllToAll, AllGather, D2D copy against the volume  */
+    double i_minimal;       /* chunks under this volume are not considered                     */
+    int32_t n_max;          /* upper bound of the chunk search (>= 1)                          */
+} monta_plan_in;
+
+typedef struct monta_plan_out {
+    double t_base;          /* untransformed AllToAll: I*(e-1)/e/(B1*r1(I))                    */
+    double t_o1;            /* Eq. 11                                                          */
+    double t_o2, t_o3;      /* best chunked times; +inf if no chunk count is admissible        */
+    int32_t n_o2, n_o3;     /* their chunk counts; 0 if none                                   */
+    int32_t strategy;       /* 1, 2 or 3: the cheapest (the lower number wins a tie)           */
+    int32_t chunks;         /* chunk count of the chosen strategy (1 for O1)                   */
+    double t_best;
+} monta_plan_out;
+
+/* Eq. 8-10 for one of n chunks; any of the outputs may be NULL. */
+int monta_plan_chunk_times(const monta_plan_in *in, int n, double *aa, double *ag, double *d2d);
+/* Algorithms 1-3. */
+int monta_plan_strategy(const monta_plan_in *in, monta_plan_out *out);
+
 /* Text for a monta_status; never NULL. */
 const char *monta_strerror(int code);
 /* The hipError_t (as int) behind the calling thread's last MONTA_ERR_HIP, 0 if none. */

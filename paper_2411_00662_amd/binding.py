@@ -46,11 +46,30 @@ class monta_ws_layout(ctypes.Structure):
                 ("off_local_rank", ctypes.c_int64)]
 
 
+class monta_curve(ctypes.Structure):
+    _fields_ = [("volume", ctypes.POINTER(ctypes.c_double)), ("eff", ctypes.POINTER(ctypes.c_double)),
+                ("n", ctypes.c_int32)]
+
+
+class monta_plan_in(ctypes.Structure):
+    _fields_ = [("traffic", ctypes.c_double), ("t", ctypes.c_int32), ("e", ctypes.c_int32),
+                ("b1", ctypes.c_double), ("b2", ctypes.c_double), ("b3", ctypes.c_double),
+                ("r1", monta_curve), ("r2", monta_curve), ("r3", monta_curve),
+                ("i_minimal", ctypes.c_double), ("n_max", ctypes.c_int32)]
+
+
+class monta_plan_out(ctypes.Structure):
+    _fields_ = [("t_base", ctypes.c_double), ("t_o1", ctypes.c_double), ("t_o2", ctypes.c_double),
+                ("t_o3", ctypes.c_double), ("n_o2", ctypes.c_int32), ("n_o3", ctypes.c_int32),
+                ("strategy", ctypes.c_int32), ("chunks", ctypes.c_int32), ("t_best", ctypes.c_double)]
+
+
 # every symbol include/monta.h declares
 EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "monta_route", "monta_dispatch",
            "monta_regather", "monta_dispatch_regather", "monta_route_dispatch_regather", "monta_combine", "monta_set_pipeline_mode",
            "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
-           "monta_profile_read", "monta_strerror", "monta_last_hip_error"]
+           "monta_profile_read", "monta_plan_chunk_times", "monta_plan_strategy", "monta_strerror",
+           "monta_last_hip_error"]
 
 _lib = None
 
@@ -83,6 +102,8 @@ def lib() -> ctypes.CDLL:
         L.monta_profile_enable.argtypes = [i32]
         L.monta_profile_reset.argtypes = []
         L.monta_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), i64p]
+        L.monta_plan_chunk_times.argtypes = [ctypes.POINTER(monta_plan_in), i32] + [ctypes.POINTER(ctypes.c_double)] * 3
+        L.monta_plan_strategy.argtypes = [ctypes.POINTER(monta_plan_in), ctypes.POINTER(monta_plan_out)]
         L.monta_strerror.argtypes = [i32]
         L.monta_strerror.restype = ctypes.c_char_p
         L.monta_last_hip_error.argtypes = []
@@ -249,3 +270,33 @@ def monta_profile_read(kernel_id: int):
     ms, n = ctypes.c_double(0), ctypes.c_int64(0)
     _check(lib().monta_profile_read(int(kernel_id), ctypes.byref(ms), ctypes.byref(n)), "monta_profile_read")
     return float(ms.value), int(n.value)
+
+
+def _curve(points):
+    """[(volume_bytes, efficiency), ...] -> (monta_curve, keep-alive arrays)."""
+    n = len(points)
+    vol = (ctypes.c_double * n)(*[float(p[0]) for p in points])
+    eff = (ctypes.c_double * n)(*[float(p[1]) for p in points])
+    return monta_curve(ctypes.cast(vol, ctypes.POINTER(ctypes.c_double)), ctypes.cast(eff, ctypes.POINTER(ctypes.c_double)), n), (vol, eff)
+
+
+def make_plan_in(traffic, t, e, b1, b2, b3, r1, r2, r3, i_minimal, n_max=1 << 16):
+    """Curves are lists of (volume in bytes, efficiency).  Returns (monta_plan_in, keep-alive tuple)."""
+    c1, k1 = _curve(r1)
+    c2, k2 = _curve(r2)
+    c3, k3 = _curve(r3)
+    return monta_plan_in(float(traffic), int(t), int(e), float(b1), float(b2), float(b3), c1, c2, c3,
+                         float(i_minimal), int(n_max)), (k1, k2, k3)
+
+
+def monta_plan_chunk_times(pin, n: int):
+    aa, ag, d2d = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib().monta_plan_chunk_times(ctypes.byref(pin), int(n), ctypes.byref(aa), ctypes.byref(ag), ctypes.byref(d2d)),
+           "monta_plan_chunk_times")
+    return aa.value, ag.value, d2d.value
+
+
+def monta_plan_strategy(pin) -> monta_plan_out:
+    out = monta_plan_out()
+    _check(lib().monta_plan_strategy(ctypes.byref(pin), ctypes.byref(out)), "monta_plan_strategy")
+    return out

@@ -7,7 +7,8 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 SRC = os.path.join(PKG, "csrc", "monta.hip")
-DEPS = [SRC, os.path.join(PKG, "csrc", "monta_kernels.hpp"), os.path.join(ROOT, "include", "monta.h")]
+DEPS = [SRC, os.path.join(PKG, "csrc", "monta_kernels.hpp"), os.path.join(PKG, "csrc", "monta_planner.hpp"),
+        os.path.join(ROOT, "include", "monta.h")]
 LIB = os.path.join(PKG, "libmonta.so")
 
 HIPCC_FLAGS = [

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "monta_kernels.hpp"
+#include "monta_planner.hpp"
 
 namespace {
 
