@@ -154,6 +154,42 @@ def combine(y: np.ndarray, gates: np.ndarray, pos_final: np.ndarray) -> np.ndarr
     return out
 
 
+def unregather(y: np.ndarray, pl: Plan, tp: int, S: int, y_stage: np.ndarray | None = None, slice_: int = -1,
+               fill: int = 0) -> np.ndarray:
+    """Expert output y [R,H] in FINAL layout -> the unit-major (STAGE) layout, block by block."""
+    y = np.ascontiguousarray(y)
+    H = y.shape[1]
+    E = pl.counts.shape[0]
+    if y_stage is None:
+        y_stage = np.full((pl.R, H), fill, dtype=y.dtype)
+    rc = _load().monta_oracle_unregather(tp, S, E, ctypes.c_int64(H * y.itemsize), _p(pl.n), _p(pl.stage_off),
+                                         _p(pl.unit_base), _p(y), _p(y_stage), slice_)
+    _check(rc, "unregather")
+    return y_stage
+
+
+def combine_staged(y_stage: np.ndarray, gates: np.ndarray, pos_stage: np.ndarray, out: np.ndarray | None = None,
+                   t0: int = 0, t1: int | None = None) -> np.ndarray:
+    """Scale-add from the unit-major layout for tokens [t0, t1)."""
+    y_stage = np.ascontiguousarray(y_stage)
+    gates = np.ascontiguousarray(gates, dtype=np.float32)
+    pos_stage = np.ascontiguousarray(pos_stage, dtype=np.int32)
+    T, k = pos_stage.shape
+    H = y_stage.shape[1]
+    t1 = T if t1 is None else t1
+    dtype = 0 if y_stage.dtype == np.float32 else 1
+    if y_stage.dtype not in (np.float32, np.uint16):
+        raise ValueError("oracle combine_staged: y_stage must be float32 or uint16 (bf16 bits)")
+    if pos_stage.max(initial=-1) >= y_stage.shape[0]:
+        raise ValueError("oracle combine_staged: position outside y_stage")
+    if out is None:
+        out = np.zeros((T, H), y_stage.dtype)
+    rc = _load().monta_oracle_combine_staged(ctypes.c_int64(t0), ctypes.c_int64(t1), H, k, dtype, _p(y_stage),
+                                             _p(gates), _p(pos_stage), _p(out))
+    _check(rc, "combine_staged")
+    return out
+
+
 def volume(pl: Plan, tp: int, S: int, row_bytes: int):
     """-> (unit_bytes [U], dest_bytes [U,ep], slice_gather_bytes [S]) as int64."""
     U, E = pl.n.shape

@@ -295,6 +295,40 @@ int monta_oracle_combine(int64_t T, int H, int k, int dtype, const void *y,
     return ORACLE_OK;
 }
 
+/* ------------------------------------------------- the second AllToAll, mirrored */
+
+/* Section "Pipelining": "The same method can be applied to the second AllToAll".  After the experts
+ * the rows travel back: the expert output y (FINAL layout, expert-major) is cut into the same
+ * (unit, expert) blocks and each block returns to its place in the unit-major layout of STAGE --
+ * the inverse of the gather + D2D copy -- so that every virtual TP rank again carries only 1/t of a
+ * slice.  slice < 0: all slices. */
+int monta_oracle_unregather(int tp, int S, int E, int64_t row_bytes, const int32_t *n,
+                            const int32_t *stage_off, const int32_t *unit_base, const void *y,
+                            void *y_stage, int slice)
+{
+    if (tp < 1 || S < 1 || E < 1 || row_bytes < 1 || slice >= S) return ORACLE_BAD_ARG;
+    const int64_t U = (int64_t)S * tp;
+    for (int64_t u = 0; u < U; ++u) {
+        if (slice >= 0 && u / tp != slice) continue;
+        for (int e = 0; e < E; ++e)
+            memcpy((char *)y_stage + (int64_t)stage_off[u * E + e] * row_bytes,
+                   (const char *)y + (int64_t)unit_base[u * E + e] * row_bytes,
+                   (size_t)((int64_t)n[u * E + e] * row_bytes));
+    }
+    return ORACLE_OK;
+}
+
+/* Unpermutation from the unit-major layout, for the tokens [t0, t1) only (one slice, or all):
+ * the same scale-add as monta_oracle_combine, rows addressed through pos_stage. */
+int monta_oracle_combine_staged(int64_t t0, int64_t t1, int H, int k, int dtype, const void *y_stage,
+                                const float *gates, const int32_t *pos_stage, void *out)
+{
+    if (t0 < 0 || t1 < t0 || H < 1 || k < 1 || (dtype != 0 && dtype != 1)) return ORACLE_BAD_ARG;
+    const int64_t bpe = dtype == 0 ? 4 : 2;
+    return monta_oracle_combine(t1 - t0, H, k, dtype, y_stage, gates + t0 * k, pos_stage + t0 * k,
+                                (char *)out + t0 * H * bpe);
+}
+
 /* ----------------------------------------------------------------- volume */
 
 /* Byte accounting of the exchange (Eq. 3 traffic I = b*s*h*BPE; Eq. 8-10 per-chunk

@@ -591,7 +591,10 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
     hipStream_t st = static_cast<hipStream_t>(stream);
     ProfScope ps(MONTA_K_COMBINE, st);
     const dim3 grid(mover_grid(s, s.T)), block(kMoverThreads);
-    const bool wide = s.vpr > 2 * kMoverThreads;     // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
+#ifndef MONTA_COMBINE_WIDE_VPR
+#define MONTA_COMBINE_WIDE_VPR (2 * kMoverThreads)
+#endif
+    const bool wide = s.vpr > MONTA_COMBINE_WIDE_VPR;   // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
     const u32x4 *yv = static_cast<const u32x4 *>(y);
     u32x4 *ov = static_cast<u32x4 *>(out);
     if (cfg->dtype == MONTA_BF16) {

@@ -455,6 +455,41 @@ def test_fully_dropped_token_gives_zero_row_and_gates_not_renormalised():
     assert (r2.out[3:] == 0).all()
 
 
+# ------------------------------------------------------- mirrored return path
+
+@pytest.mark.parametrize("dtype", [FP32, BF16])
+def test_unregather_inverts_regather_and_staged_combine_equals_direct(dtype):
+    w = Workload("t", 240, 24, dtype, 6, 3, 3, 4, 3, 0.7)
+    logits, x = workloads.make_inputs(w, seed=12)
+    logits[:, 4] += 1.5
+    r = oracle.forward(logits, x, k=3, ep=3, tp=4, S=3, cf=0.7)
+    assert (r.plan.pos_final < 0).any()
+    # identity experts: the way back reproduces the send buffer exactly
+    np.testing.assert_array_equal(oracle.unregather(r.final, r.plan, 4, 3), r.stage)
+    # arbitrary expert output: explicit gather through the two position tables
+    rng = np.random.default_rng(2)
+    y = rng.standard_normal((r.plan.R, w.hidden), dtype=np.float32)
+    if dtype == BF16:
+        y = workloads.f32_to_bf16_bits(y)
+    ys = oracle.unregather(y, r.plan, 4, 3, fill=0)
+    m = r.plan.pos_final >= 0
+    expect = np.zeros_like(y)
+    expect[r.plan.pos_stage[m]] = y[r.plan.pos_final[m]]
+    np.testing.assert_array_equal(ys, expect)
+    # slice by slice, any order, only the slice's rows / tokens are touched
+    ys2 = np.full_like(y, 7)
+    out2 = np.full((w.tokens, w.hidden), 9, dtype=y.dtype)
+    per_slice = w.tokens // 3
+    for j in (1, 2, 0):
+        oracle.unregather(y, r.plan, 4, 3, y_stage=ys2, slice_=j)
+        oracle.combine_staged(ys2, r.gates, r.plan.pos_stage, out=out2, t0=j * per_slice, t1=(j + 1) * per_slice)
+    np.testing.assert_array_equal(ys2, ys)
+    # the mirrored path gives the very bits of the direct unpermutation (same sum, same order)
+    direct = oracle.combine(y, r.gates, r.plan.pos_final)
+    np.testing.assert_array_equal(out2, direct)
+    np.testing.assert_array_equal(oracle.combine_staged(ys, r.gates, r.plan.pos_stage), direct)
+
+
 # ------------------------------------------------------------------- volume
 
 def read_table8():
