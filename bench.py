@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--graph", type=int, default=0, help="replay the step from a captured HIP graph (1) or launch eagerly (0)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run the plain copy kernel on buffers of this size (profiler byte-counter calibration)")
+    ap.add_argument("--return-path", default="direct", choices=["direct", "mirror"],
+                    help="direct: combine reads the expert output in FINAL layout (the headline path); mirror: the "
+                         "second AllToAll mirrored (unregather + staged combine pipeline), 2R more rows moved")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     args = ap.parse_args()
@@ -94,9 +97,15 @@ def main():
 
     stream = torch.cuda.Stream()          # default priority; the whole step is enqueued on it
 
+    mirror = args.return_path == "mirror"
+    y_stage = torch.empty_like(b.stage) if mirror else None
+
     def step():
         m.monta_route_dispatch_regather(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, b.ws, stream)
-        m.monta_combine(cfg, b.final, b.gates, b.out, b.ws, stream)
+        if mirror:
+            m.monta_unregather_combine(cfg, b.final, y_stage, b.gates, b.out, b.ws, stream)
+        else:
+            m.monta_combine(cfg, b.final, b.gates, b.out, b.ws, stream)
 
     torch.cuda.synchronize()
     use_graph = bool(args.graph)
@@ -135,6 +144,10 @@ def main():
 
     tabs = m.read_tables(cfg, b.ws)
     ab = algorithmic_bytes(w, tabs)
+    if mirror:
+        ab["total"] += 2 * ab["R"] * ab["row"]
+        ab["unregather_s"] = ab["regather_s"]
+        ab["combine_s"] = [ab["regather_s"][j] // 2 + (w.tokens // w.slices) * ab["row"] for j in range(w.slices)]
     eff_gbps = ab["total"] / (ms_per_step * 1e-3) / 1e9
 
     # ---- per-kernel durations: HIP events around every launch, on the launching stream, eager launches
@@ -173,7 +186,15 @@ def main():
         if "pack_regather" in kernels:
             tot = sum(ab["pack_s"][j] + ab["regather_s"][j - 1] for j in range(1, S))
             per_launch["pack_regather"] = tot / (S - 1)
-        movers = [kname for kname in ("pack", "regather", "pack_regather", "combine", "plan_pack") if kname in kernels]
+        if mirror:
+            S_ = w.slices
+            per_launch["unregather"] = ab["unregather_s"][0]
+            per_launch["combine"] = ab["combine_s"][S_ - 1]
+            if S_ > 1:
+                per_launch["unregather_combine"] = sum(ab["unregather_s"][j] + ab["combine_s"][j - 1]
+                                                       for j in range(1, S_)) / (S_ - 1)
+        movers = [kname for kname in ("pack", "regather", "pack_regather", "combine", "plan_pack", "unregather",
+                                      "unregather_combine") if kname in kernels]
         dom = max(movers, key=lambda kname: kernels[kname]["us_per_step"])
         achieved = per_launch[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e9
         # HBM-side bytes per launch of that kernel from rocprofv3 counters (profiles/traffic.json, written by
@@ -230,7 +251,8 @@ def main():
         "config": {"workload": w.name, "tokens": w.tokens, "hidden": w.hidden, "experts": w.experts,
                    "top_k": w.top_k, "ep": w.ep, "tp": w.tp, "slices": w.slices,
                    "capacity_factor": w.capacity_factor, "kept_rows": ab["R"], "alive_tokens": ab["alive"],
-                   "pipeline_mode": mode, "hip_graph": use_graph, "parallelism": "1 GPU, virtual ep/tp"},
+                   "pipeline_mode": mode, "hip_graph": use_graph, "return_path": args.return_path,
+                   "parallelism": "1 GPU, virtual ep/tp"},
         "effective_GBps": round(eff_gbps, 1), "pct_of_hbm_peak": round(100 * eff_gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_bytes_per_step": int(ab["total"]),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,

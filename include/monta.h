@@ -164,6 +164,25 @@ int monta_route_dispatch_regather(const monta_cfg *cfg, const float *logits, con
 int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void *out, const void *ws,
                   void *stream);
 
+/* ---- the second AllToAll, mirrored (section "Pipelining": "The same method can be applied to the
+ * second AllToAll") ----
+ * The expert output y [max_rows][H] (FINAL layout) travels back the way the tokens came: block by
+ * block into the unit-major layout of STAGE, so that every virtual TP rank again carries only 1/tp
+ * of a slice, and from there into token order.  The result is bit-identical to monta_combine. */
+
+/* Row row_map[s] of y goes to row s of y_stage, for the STAGE rows of slice `slice` (all if -1). */
+int monta_unregather(const monta_cfg *cfg, const void *y, void *y_stage, const void *ws, int slice, void *stream);
+
+/* Scale-add from the unit-major layout: out[t] = sum over kept j of gates[t][j] * y_stage[pos_stage[t][j]]
+ * for the tokens of slice `slice` (all if -1); same arithmetic as monta_combine. */
+int monta_combine_staged(const monta_cfg *cfg, const void *y_stage, const float *gates, void *out, const void *ws,
+                         int slice, void *stream);
+
+/* The return pipeline on one stream: launch j fetches slice j back and, in disjoint workgroups of the
+ * same grid, combines the tokens of slice j-1 (S+1 launches). */
+int monta_unregather_combine(const monta_cfg *cfg, const void *y, void *y_stage, const float *gates, void *out,
+                             const void *ws, void *stream);
+
 /* Pipeline realisations for monta_dispatch_regather:
  *   0  two streams: packs on `stream`, regathers on a library-owned side stream
  *      (default priority), one event per slice, joined back into `stream`;
@@ -216,7 +235,9 @@ enum monta_kernel_id {
     MONTA_K_COMBINE = 5,
     MONTA_K_COPY = 6,
     MONTA_K_PLAN_PACK = 7,  /* plan + positions + pack of slice 0 in one grid */
-    MONTA_K_COUNT = 8
+    MONTA_K_UNREGATHER = 8,
+    MONTA_K_UNREGATHER_COMBINE = 9, /* co-scheduled grid of the return pipeline */
+    MONTA_K_COUNT = 10
 };
 int monta_profile_enable(int on);
 int monta_profile_reset(void);

@@ -15,6 +15,10 @@
 #include "monta_kernels.hpp"
 #include "monta_planner.hpp"
 
+#ifndef MONTA_COMBINE_WIDE_VPR
+#define MONTA_COMBINE_WIDE_VPR (2 * kMoverThreads)
+#endif
+
 namespace {
 
 using namespace monta;
@@ -591,9 +595,6 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
     hipStream_t st = static_cast<hipStream_t>(stream);
     ProfScope ps(MONTA_K_COMBINE, st);
     const dim3 grid(mover_grid(s, s.T)), block(kMoverThreads);
-#ifndef MONTA_COMBINE_WIDE_VPR
-#define MONTA_COMBINE_WIDE_VPR (2 * kMoverThreads)
-#endif
     const bool wide = s.vpr > MONTA_COMBINE_WIDE_VPR;   // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
     const u32x4 *yv = static_cast<const u32x4 *>(y);
     u32x4 *ov = static_cast<u32x4 *>(out);
@@ -605,6 +606,105 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
         else hipLaunchKernelGGL((combine_kernel<false, 2>), grid, block, 0, st, yv, gates, ov, p, s);
     }
     HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+// mirrored return path -------------------------------------------------------------------------
+
+int monta_unregather(const monta_cfg *cfg, const void *y, void *y_stage, const void *ws, int slice, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (slice < -1 || slice >= cfg->slices) return MONTA_ERR_INVALID;
+    if ((rc = check_act_ptrs(y, y_stage))) return rc;
+    if (y == y_stage) return MONTA_ERR_INVALID;
+    if ((rc = check_ws(ws))) return rc;
+    const Shape &s = g.s;
+    const PlanPtrs p = plan_ptrs(g, ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int u0 = slice < 0 ? 0 : slice * s.tp;
+    const int u1 = slice < 0 ? s.U : (slice + 1) * s.tp;
+    ProfScope ps(MONTA_K_UNREGATHER, st);
+    hipLaunchKernelGGL(unregather_kernel, dim3(regather_grid(s, slice_rows_bound(g, slice < 0 ? s.S : 1))),
+                       dim3(kMoverThreads), 0, st, static_cast<const u32x4 *>(y), static_cast<u32x4 *>(y_stage), p, s,
+                       u0, u1);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+namespace {
+
+// launches unregather(units [u0,u1)) and / or combine of tokens [t0, t0+nt) from the unit-major layout
+int launch_unregather_combine(const Geometry &g, const PlanPtrs &p, int dtype, const void *y, void *y_stage,
+                              const float *gates, void *out, int u0, int u1, int t0, int nt, hipStream_t st)
+{
+    const Shape &s = g.s;
+    const int n_unreg = u0 < u1 ? regather_grid(s, slice_rows_bound(g, (u1 - u0) / s.tp)) : 0;
+    const int n_comb = nt > 0 ? mover_grid(s, nt) : 0;
+    if (n_unreg + n_comb == 0) return MONTA_OK;
+    const bool wide = s.vpr > MONTA_COMBINE_WIDE_VPR;
+    const u32x4 *yv = static_cast<const u32x4 *>(y);
+    u32x4 *sv = static_cast<u32x4 *>(y_stage), *ov = static_cast<u32x4 *>(out);
+    const dim3 grid(n_unreg + n_comb), block(kMoverThreads);
+    ProfScope ps(n_unreg && n_comb ? MONTA_K_UNREGATHER_COMBINE : (n_unreg ? MONTA_K_UNREGATHER : MONTA_K_COMBINE), st);
+    if (dtype == MONTA_BF16) {
+        if (wide) hipLaunchKernelGGL((unregather_combine_kernel<true, 4>), grid, block, 0, st, yv, sv, gates, ov, p, s, u0, u1, t0, nt, n_unreg);
+        else hipLaunchKernelGGL((unregather_combine_kernel<true, 2>), grid, block, 0, st, yv, sv, gates, ov, p, s, u0, u1, t0, nt, n_unreg);
+    } else {
+        if (wide) hipLaunchKernelGGL((unregather_combine_kernel<false, 4>), grid, block, 0, st, yv, sv, gates, ov, p, s, u0, u1, t0, nt, n_unreg);
+        else hipLaunchKernelGGL((unregather_combine_kernel<false, 2>), grid, block, 0, st, yv, sv, gates, ov, p, s, u0, u1, t0, nt, n_unreg);
+    }
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+int check_staged_combine(const monta_cfg *cfg, Geometry *g, const void *y_stage, const float *gates, void *out,
+                         const void *ws)
+{
+    int rc = validate(cfg, g);
+    if (rc) return rc;
+    if (!gates) return MONTA_ERR_NULL;
+    if (misaligned(gates, 4)) return MONTA_ERR_ALIGN;
+    if ((rc = check_act_ptrs(y_stage, out))) return rc;
+    if (y_stage == out) return MONTA_ERR_INVALID;
+    return check_ws(ws);
+}
+
+}  // namespace
+
+int monta_combine_staged(const monta_cfg *cfg, const void *y_stage, const float *gates, void *out, const void *ws,
+                         int slice, void *stream)
+{
+    Geometry g;
+    int rc = check_staged_combine(cfg, &g, y_stage, gates, out, ws);
+    if (rc) return rc;
+    if (slice < -1 || slice >= cfg->slices) return MONTA_ERR_INVALID;
+    const Shape &s = g.s;
+    const int per_slice = s.tp * s.Tu;
+    const int t0 = slice < 0 ? 0 : slice * per_slice, nt = slice < 0 ? s.T : per_slice;
+    return launch_unregather_combine(g, plan_ptrs(g, ws), cfg->dtype, y_stage, const_cast<void *>(y_stage), gates, out,
+                                     0, 0, t0, nt, static_cast<hipStream_t>(stream));
+}
+
+int monta_unregather_combine(const monta_cfg *cfg, const void *y, void *y_stage, const float *gates, void *out,
+                             const void *ws, void *stream)
+{
+    Geometry g;
+    int rc = check_staged_combine(cfg, &g, y_stage, gates, out, ws);
+    if (rc) return rc;
+    if ((rc = check_act_ptrs(y, y_stage))) return rc;
+    if (y == y_stage || y == out) return MONTA_ERR_INVALID;
+    const Shape &s = g.s;
+    const PlanPtrs p = plan_ptrs(g, ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int per_slice = s.tp * s.Tu;
+    // launch j fetches slice j back and combines the tokens of slice j-1
+    for (int j = 0; j <= s.S; ++j) {
+        const int u0 = j < s.S ? j * s.tp : 0, u1 = j < s.S ? (j + 1) * s.tp : 0;
+        const int t0 = j > 0 ? (j - 1) * per_slice : 0, nt = j > 0 ? per_slice : 0;
+        if ((rc = launch_unregather_combine(g, p, cfg->dtype, y, y_stage, gates, out, u0, u1, t0, nt, st))) return rc;
+    }
     return MONTA_OK;
 }
 

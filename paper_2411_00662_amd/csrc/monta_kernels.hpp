@@ -610,8 +610,9 @@ __device__ __forceinline__ void pack_rows(const u32x4 *__restrict__ x, u32x4 *__
 }
 
 // STAGE rows [r0, r1) go to FINAL rows row_map[.]
-template <bool NTL, bool NTS>
-__device__ __forceinline__ void regather_rows_t(const u32x4 *__restrict__ stage, u32x4 *__restrict__ fin,
+// REVERSE: the other direction (the mirrored return path): row row_map[r] of `fin` goes to row r of `stage`.
+template <bool REVERSE, bool NTL, bool NTS>
+__device__ __forceinline__ void regather_rows_t(u32x4 *stage, u32x4 *fin,
                                               const int32_t *__restrict__ row_map, const Shape &s, int r0,
                                               int r1, int wg, int nwg)
 {
@@ -623,8 +624,8 @@ __device__ __forceinline__ void regather_rows_t(const u32x4 *__restrict__ stage,
     for (int r = r0 + wg * rows_per_wg + sub; r < r1; r += nwg * rows_per_wg) {
         const int fr = row_map[r];
         if ((unsigned)fr >= (unsigned)s.max_rows) continue;
-        const u32x4 *src = stage + (size_t)r * vpr;
-        u32x4 *dst = fin + (size_t)fr * vpr;
+        const u32x4 *src = REVERSE ? fin + (size_t)fr * vpr : stage + (size_t)r * vpr;
+        u32x4 *dst = REVERSE ? stage + (size_t)r * vpr : fin + (size_t)fr * vpr;
         for (int v0 = lane; v0 < vpr; v0 += lpr * kVecInFlight) {
             u32x4 val[kVecInFlight];
 #pragma unroll
@@ -642,7 +643,19 @@ __device__ __forceinline__ void regather_rows(const u32x4 *__restrict__ stage, u
                                               int r1, int wg, int nwg)
 {
     with_policy(s.cache & NT_REG_LD, s.cache & NT_REG_ST, [&](auto l, auto st) {
-        regather_rows_t<decltype(l)::value, decltype(st)::value>(stage, fin, row_map, s, r0, r1, wg, nwg);
+        regather_rows_t<false, decltype(l)::value, decltype(st)::value>(const_cast<u32x4 *>(stage), fin, row_map, s, r0,
+                                                                        r1, wg, nwg);
+    });
+}
+
+// the mirrored direction: expert output y (FINAL layout) back to the unit-major layout
+__device__ __forceinline__ void unregather_rows(const u32x4 *__restrict__ y, u32x4 *__restrict__ y_stage,
+                                                const int32_t *__restrict__ row_map, const Shape &s, int r0,
+                                                int r1, int wg, int nwg)
+{
+    with_policy(s.cache & NT_REG_LD, s.cache & NT_REG_ST, [&](auto l, auto st) {
+        regather_rows_t<true, decltype(l)::value, decltype(st)::value>(y_stage, const_cast<u32x4 *>(y), row_map, s, r0,
+                                                                       r1, wg, nwg);
     });
 }
 
@@ -781,17 +794,20 @@ __device__ __forceinline__ unsigned int f64_to_bf16_rne(double d)
 // to 16 KiB.  Tokens are walked from the last to the first: the FINAL rows written
 // most recently (by the last slices) are read first, while the memory-side cache
 // still holds them.  A dropped pair is skipped; a token with no kept pair writes zeros.
+// `pos_table` is pos_final (y in FINAL layout) or pos_stage (y in the unit-major layout of the mirrored
+// return path); tokens [t0, t0+nt) are combined by workgroups wg of nwg.
 template <bool BF16, int NV, bool NTL, bool NTS>
 __device__ __forceinline__ void combine_rows_t(const u32x4 *__restrict__ y, const float *__restrict__ gates,
-                                               u32x4 *__restrict__ out, const PlanPtrs &p, const Shape &s)
+                                               u32x4 *__restrict__ out, const int32_t *__restrict__ pos_table,
+                                               const Shape &s, int t0, int nt, int wg, int nwg)
 {
     constexpr int NF = BF16 ? 8 : 4;            // accumulators per vector
     const int lpr = s.lpr, vpr = s.vpr, k = s.k;
     const int rows_per_wg = kMoverThreads / lpr;
     const int sub = threadIdx.x / lpr, lane = threadIdx.x - sub * lpr;
-    for (int i = blockIdx.x * rows_per_wg + sub; i < s.T; i += gridDim.x * rows_per_wg) {
-        const int t = s.T - 1 - i;
-        const int32_t *pos = p.pos_final + (size_t)t * k;
+    for (int i = wg * rows_per_wg + sub; i < nt; i += nwg * rows_per_wg) {
+        const int t = t0 + nt - 1 - i;
+        const int32_t *pos = pos_table + (size_t)t * k;
         const float *g = gates + (size_t)t * k;
         u32x4 *dst = out + (size_t)t * vpr;
         for (int v0 = lane; v0 < vpr; v0 += lpr * NV) {
@@ -848,8 +864,51 @@ __global__ __launch_bounds__(kMoverThreads) void combine_kernel(const u32x4 *__r
                                                                 u32x4 *__restrict__ out, PlanPtrs p, Shape s)
 {
     with_policy(s.cache & NT_COMB_LD, s.cache & NT_COMB_ST, [&](auto l, auto st) {
-        combine_rows_t<BF16, NV, decltype(l)::value, decltype(st)::value>(y, gates, out, p, s);
+        combine_rows_t<BF16, NV, decltype(l)::value, decltype(st)::value>(y, gates, out, p.pos_final, s, 0, s.T,
+                                                                          blockIdx.x, gridDim.x);
     });
+}
+
+// ---- the second AllToAll, mirrored: y (FINAL layout) -> unit-major layout -> token order, slice by slice
+
+__global__ __launch_bounds__(kMoverThreads) void unregather_kernel(const u32x4 *__restrict__ y,
+                                                                   u32x4 *__restrict__ y_stage, PlanPtrs p, Shape s,
+                                                                   int u0, int u1)
+{
+    unregather_rows(y, y_stage, p.row_map, s, p.unit_rows[u0], p.unit_rows[u1], blockIdx.x, gridDim.x);
+}
+
+// One grid, up to two jobs in disjoint, interleaved workgroups: the unit-major rows of units [u0, u1)
+// are fetched back from y (skipped if u0 >= u1) while the tokens [t0, t0+nt) of the slice before are
+// combined from rows fetched by the previous launch (skipped if nt == 0).
+template <bool BF16, int NV>
+__global__ __launch_bounds__(kMoverThreads) void unregather_combine_kernel(const u32x4 *__restrict__ y,
+                                                                           u32x4 *y_stage,
+                                                                           const float *__restrict__ gates,
+                                                                           u32x4 *__restrict__ out, PlanPtrs p,
+                                                                           Shape s, int u0, int u1, int t0, int nt,
+                                                                           int n_unreg_wg)
+{
+    const int n_comb_wg = gridDim.x - n_unreg_wg;
+    const int bid = blockIdx.x;
+    const int pairs = n_unreg_wg < n_comb_wg ? n_unreg_wg : n_comb_wg;
+    bool is_unreg;
+    int idx;
+    if (bid < 2 * pairs) {
+        is_unreg = (bid & 1) == 0;
+        idx = bid >> 1;
+    } else {
+        is_unreg = n_unreg_wg > n_comb_wg;
+        idx = bid - pairs;
+    }
+    if (is_unreg) {
+        if (u0 < u1) unregather_rows(y, y_stage, p.row_map, s, p.unit_rows[u0], p.unit_rows[u1], idx, n_unreg_wg);
+    } else if (nt > 0) {
+        with_policy(s.cache & NT_COMB_LD, s.cache & NT_COMB_ST, [&](auto l, auto st) {
+            combine_rows_t<BF16, NV, decltype(l)::value, decltype(st)::value>(y_stage, gates, out, p.pos_stage, s, t0,
+                                                                              nt, idx, n_comb_wg);
+        });
+    }
 }
 
 // ------------------------------------------------------------- plain copy
