@@ -47,6 +47,8 @@ int pow2ceil(int v)
     return p;
 }
 
+constexpr size_t kRouteLdsBudget = 120 * 1024;
+
 struct Geometry {
     Shape s;
     int64_t max_rows;
@@ -107,10 +109,11 @@ int validate(const monta_cfg *c, Geometry *g)
     const int lpr_max = kMoverThreads;
 #endif
     s.lpr = pow2ceil(s.vpr) < lpr_max ? pow2ceil(s.vpr) : lpr_max;
-    // route workgroup: as many tokens as fit 60 KiB of LDS, at most 256, no more than a unit needs
+    // route workgroup: as many tokens as fit the LDS budget (gfx950 gives a workgroup up to 160 KiB),
+    // at most 256, no more than a unit needs
     int TB = 256;
-    while (TB > 32 && (route_lds_bytes(TB, s.E, s.k) > 60 * 1024 || TB / 2 >= s.Tu)) TB >>= 1;
-    if (route_lds_bytes(TB, s.E, s.k) > 60 * 1024) return MONTA_ERR_UNSUPPORTED;
+    while (TB > 32 && (route_lds_bytes(TB, s.E, s.k) > kRouteLdsBudget || TB / 2 >= s.Tu)) TB >>= 1;
+    if (route_lds_bytes(TB, s.E, s.k) > kRouteLdsBudget) return MONTA_ERR_UNSUPPORTED;
     s.TB = TB;
     s.bpu = (s.Tu + TB - 1) / TB;
     const int64_t nb = (int64_t)s.bpu * U;
@@ -167,6 +170,7 @@ void fill_layout(const Geometry &g, monta_ws_layout *L)
     L->off_block_counts = take((int64_t)s.num_blocks * s.E);
     L->off_block_base = take((int64_t)s.num_blocks * s.E);
     L->off_local_rank = take((int64_t)s.T * s.k);
+    L->off_final_order = take(g.max_rows);
     L->ws_bytes = off;
 }
 
@@ -192,6 +196,7 @@ PlanPtrs plan_ptrs(const Geometry &g, const void *ws)
     p.block_counts = at(L.off_block_counts);
     p.block_base = at(L.off_block_base);
     p.local_rank = at(L.off_local_rank);
+    p.final_order = at(L.off_final_order);
     return p;
 }
 
@@ -396,6 +401,13 @@ int check_act_ptrs(const void *a, const void *b)
 int launch_route(const Geometry &g, const PlanPtrs &p, const float *logits, int32_t *topk_idx, float *gates,
                  hipStream_t st)
 {
+    static std::atomic<int> lds_opt_in{0};
+    if (g.route_lds > 48 * 1024 && !lds_opt_in.load()) {
+        // dynamic LDS above the default limit has to be asked for once per kernel
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(route_plan_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRouteLdsBudget));
+        lds_opt_in.store(1);
+    }
     ProfScope ps(MONTA_K_ROUTE, st);
     hipLaunchKernelGGL(route_plan_kernel, dim3(g.s.num_blocks), dim3(g.route_threads), g.route_lds, st, logits,
                        topk_idx, gates, p, g.s);
