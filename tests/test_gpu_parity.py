@@ -220,8 +220,8 @@ def test_skewed_full_size(m):
     _say("skewed oracle")
     ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor)
     assert ref.plan.R == 233178 and ref.plan.alive == 63030
-    _say("skewed gpu mode 1")
-    got = run_gpu(m, w, logits, x, mode=1)
+    _say("skewed gpu mode 1, the calls bench.py times")
+    got = run_gpu(m, w, logits, x, mode=1, how="fused_call")
     # full buffers are 7 GiB each on the host: compare the live part, then the canary on a sample of the tail
     R = ref.plan.R
     for name in ("stage_full", "final_full"):
@@ -373,3 +373,62 @@ def test_copy_kernel_and_profile_counters(m):
     assert torch.equal(dst, src)
     m.monta_profile_reset()
     assert m.monta_profile_read(6) == (0.0, 0)
+
+
+def test_hip_graph_replays_match_eager(m):
+    """The step captured in a HIP graph (no memset nodes: the library clears its counters in kernels) and
+    replayed several times, with eager work and synchronisations in between, gives the eager bits every time."""
+    import torch
+    from paper_2411_00662_amd import buffers as bufs
+    w = Workload("graph", 4096, 1024, BF16, 8, 2, 4, 2, 4, 0.8, zipf_s=0.6)
+    cfg = cfg_of(m, w)
+    m.monta_set_pipeline_mode(1)
+    inputs = [workloads.make_inputs(w, seed=s) for s in (1, 2, 3)]
+    b = m.alloc_buffers(cfg, *inputs[0], canary=0)
+    stream = torch.cuda.Stream()
+
+    def step():
+        m.monta_route_dispatch_regather(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, b.ws, stream)
+        m.monta_combine(cfg, b.final, b.gates, b.out, b.ws, stream)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        tabs = m.read_tables(cfg, b.ws)
+        return (tabs["R"], tabs["alive"], tabs["pos_final"].copy(), tabs["pos_stage"].copy(), b.topk_idx.cpu().numpy(),
+                bufs.to_host_act(cfg, b.final, tabs["R"]).copy(), bufs.to_host_act(cfg, b.out).copy())
+
+    def load(i):
+        logits, x = inputs[i]
+        b.logits.copy_(torch.from_numpy(logits).cuda())
+        b.x.copy_(torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16))
+        torch.cuda.synchronize()
+
+    eager = []
+    for i in range(3):
+        load(i)
+        with torch.cuda.stream(stream):
+            step()
+        eager.append(snapshot())
+    load(0)
+    with torch.cuda.stream(stream):
+        step()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+    for rep in range(2):
+        for i in (2, 0, 1):
+            _say(f"graph replay rep={rep} input={i}")
+            load(i)
+            b.out.zero_()
+            b.final.zero_()
+            graph.replay()
+            got = snapshot()
+            for a, e in zip(got, eager[i]):
+                np.testing.assert_array_equal(a, e)
+            with torch.cuda.stream(stream):          # eager work between the replays
+                step()
+            for a, e in zip(snapshot(), eager[i]):
+                np.testing.assert_array_equal(a, e)
+    ref = oracle.forward(*inputs[1], k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor)
+    assert eager[1][0] == ref.plan.R and np.array_equal(eager[1][5], ref.final)
