@@ -312,7 +312,7 @@ def test_non_identity_experts_and_shared_gates(m):
     for dtype in (FP32, BF16):
         w = Workload("y", 1024, 512, dtype, 8, 4, 4, 2, 2, 0.6, zipf_s=1.0)
         logits, x = workloads.make_inputs(w, seed=9)
-        ref = oracle.forward(logits, x, k=4, ep=4, tp=2, S=2, cf=0.6)
+        ref = oracle.forward(logits, x, k=4, ep=4, tp=2, S=2, cf=w.capacity_factor)
         rng = np.random.default_rng(1)
         y = rng.standard_normal((ref.plan.R, w.hidden), dtype=np.float32) * 3
         if dtype == BF16:
@@ -348,7 +348,7 @@ def test_workspace_reuse_across_different_inputs(m):
         m.monta_dispatch_regather(cfg, b.x, b.stage, b.final, b.ws)
         m.monta_combine(cfg, b.final, b.gates, b.out, b.ws)
         torch.cuda.synchronize()
-        ref = oracle.forward(logits, x, k=2, ep=2, tp=2, S=4, cf=0.9)
+        ref = oracle.forward(logits, x, k=2, ep=2, tp=2, S=4, cf=w.capacity_factor)
         tabs = m.read_tables(cfg, b.ws)
         assert tabs["R"] == ref.plan.R and tabs["alive"] == ref.plan.alive
         np.testing.assert_array_equal(tabs["pos_stage"], ref.plan.pos_stage)
@@ -432,3 +432,31 @@ def test_hip_graph_replays_match_eager(m):
                 np.testing.assert_array_equal(a, e)
     ref = oracle.forward(*inputs[1], k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor)
     assert eager[1][0] == ref.plan.R and np.array_equal(eager[1][5], ref.final)
+
+
+def test_random_small_shapes(m):
+    """Seeded random problems: every entry-point combination must agree with the oracle on each."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 40:
+        E = int(rng.integers(1, 49))
+        k = int(rng.integers(1, min(E, 6) + 1))
+        ep = int(rng.choice([d for d in range(1, E + 1) if E % d == 0]))
+        tp, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        Tu = int(rng.integers(1, 300))
+        T = Tu * tp * S
+        dtype = int(rng.integers(0, 2))
+        H = int(rng.integers(1, 80)) * (4 if dtype == FP32 else 8)
+        cf = float(rng.choice([0.0, 0.3, 0.75, 1.0, 1.5]))
+        renorm = int(rng.integers(0, 2))
+        w = Workload("rand", T, H, dtype, E, k, ep, tp, S, cf, renorm=renorm, zipf_s=float(rng.choice([0.0, 0.7])))
+        logits, x = workloads.make_inputs(w, seed=1000 + done)
+        mode = int(rng.integers(0, 3))
+        how = str(rng.choice(["pipeline", "all", "slices_reversed", "fused_call"]))
+        plan_mode = int(rng.choice([-1, 0]))
+        cache = int(rng.integers(-1, 64))
+        _say(f"random {done}: T={T} H={H} dtype={dtype} E={E} k={k} ep={ep} tp={tp} S={S} cf={cf} renorm={renorm} "
+             f"mode={mode} how={how} plan_mode={plan_mode} cache={cache}")
+        got = run_gpu(m, w, logits, x, mode=mode, how=how, plan_mode=plan_mode, cache=cache)
+        check_against_oracle(w, logits, x, got)
+        done += 1

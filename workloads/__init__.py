@@ -42,6 +42,11 @@ class Workload:
     zipf_s: float = 0.0    # > 0 => add -s*ln(e+1) to the logits
     seed: int = 0
 
+    def __post_init__(self):
+        # the C ABI carries the capacity factor as fp32: keep the fp32-representable value here, so that
+        # every consumer of a workload (CPU or GPU side) is handed exactly the same number
+        object.__setattr__(self, "capacity_factor", float(np.float32(self.capacity_factor)))
+
     @property
     def bpe(self) -> int:
         return 4 if self.dtype == FP32 else 2
