@@ -54,7 +54,8 @@ struct Geometry {
     int64_t max_rows;
     int64_t row_bytes;
     size_t route_lds;
-    int route_threads;
+    int route_threads;   // workgroup size of the route kernel: TB * lanes per token
+    int plan_threads;    // workgroup size of the positions kernels: one lane per token
 };
 
 // Per-expert capacity: C = min(T, ceil(cf*T*k/E)), cf = 0 meaning "no drop".
@@ -122,7 +123,12 @@ int validate(const monta_cfg *c, Geometry *g)
     // the per-workgroup rebuild of the scans reads num_blocks*E counters in every workgroup
     s.fast_plan = (g_plan_mode.load() != 0 && nb * s.E <= 65536) ? 1 : 0;
     g->route_lds = route_lds_bytes(TB, s.E, s.k);
-    g->route_threads = TB < kWave ? kWave : TB;
+    g->plan_threads = TB < kWave ? kWave : TB;
+    // lanes per token in the route kernel: each lane should still scan at least 8 experts
+    int rl = 1;
+    while (rl < 8 && s.E / (2 * rl) >= 8 && TB * 2 * rl <= 1024) rl *= 2;
+    s.rl = rl;
+    g->route_threads = TB * rl < kWave ? kWave : TB * rl;
     const int64_t tk = c->tokens * (int64_t)c->top_k, ec = (int64_t)c->experts * s.C;
     g->max_rows = tk < ec ? tk : ec;
     s.max_rows = (int32_t)g->max_rows;
@@ -481,7 +487,7 @@ int monta_route(const monta_cfg *cfg, const float *logits, int32_t *topk_idx, fl
     {
         ProfScope ps(MONTA_K_POSITIONS, st);
         if (s.fast_plan)
-            hipLaunchKernelGGL(plan_positions_kernel, dim3(s.num_blocks), dim3(g.route_threads), 0, st, topk_idx, p, s);
+            hipLaunchKernelGGL(plan_positions_kernel, dim3(s.num_blocks), dim3(g.plan_threads), 0, st, topk_idx, p, s);
         else
             hipLaunchKernelGGL(positions_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, topk_idx, p, s);
         HIP_TRY(hipGetLastError());

@@ -45,6 +45,7 @@ struct Shape {
     int32_t lpr;       // lanes cooperating on one row in the movers (power of two <= kMoverThreads)
     int32_t max_rows;  // rows STAGE / FINAL hold; every row index read from a table is checked against it
     int32_t cache;     // CachePolicy bits: which streams of the movers use non-temporal accesses
+    int32_t rl;        // lanes that share one token in the route kernel (1, 2, 4 or 8)
     int32_t fast_plan; // 1: plan_positions_kernel rebuilds the scans per workgroup; 0: ticketed scan + positions_kernel
 };
 
@@ -95,11 +96,12 @@ __device__ __forceinline__ void with_policy(bool ntl, bool nts, F f)
 
 // ------------------------------------------------------------ route + plan
 
-// One workgroup routes TB consecutive tokens of ONE unit, one token per lane.
+// One workgroup routes TB consecutive tokens of ONE unit; s.rl lanes share a token (1 for few experts).
 //  1. the [nt][E] logits tile is staged in LDS (coalesced, odd row stride);
 //  2. k selection passes per token over its LDS row: the next winner is the largest
 //     element that comes after the previous winner in (value desc, index asc) order,
-//     so ties resolve to the lower index with no "taken" mask;
+//     so ties resolve to the lower index with no "taken" mask; with s.rl > 1 each lane
+//     scans every s.rl-th expert and the lanes of a token agree by xor-shuffles;
 //  3. gates in fp64 from the winners' logits, one rounding to fp32;
 //  4. every lane ORs its bit into mask[expert][wave] in LDS; popcounts of those
 //     masks give the workgroup's expert histogram and each pair's stable rank inside
@@ -109,7 +111,7 @@ __device__ __forceinline__ void with_policy(bool ntl, bool nts, F f)
 //     over workgroups per expert, capacity clip, expert offsets, per-unit block
 //     tables.  With s.fast_plan == 1 plan_positions_kernel does that instead.
 // No atomics decide a position: the result is deterministic.
-__global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict__ logits,
+__global__ __launch_bounds__(1024) void route_plan_kernel(const float *__restrict__ logits,
                                                          int32_t *__restrict__ topk_idx,
                                                          float *__restrict__ gates, PlanPtrs p, Shape s)
 {
@@ -145,11 +147,17 @@ __global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict
     }
     __syncthreads();
 
-    const int t = t_begin + tid;
-    const bool active = tid < nt;
+    // token handled by this lane, and which of the token's s.rl lanes it is
+    const int L = s.rl;
+    const int tok = tid / L, sub = tid - tok * L;
+    const int tword = tok >> 6;                     // mask word and bit of the token inside the workgroup
+    const unsigned long long tbit = 1ull << (tok & 63);
+    const int t = t_begin + tok;
+    const bool active = tok < nt;
+    const bool leader = active && sub == 0;
     if (active) {
-        const float *row = s_l + tid * stride;
-        int *sel = s_sel + tid * k;
+        const float *row = s_l + tok * stride;
+        int *sel = s_sel + tok * k;
         float pv = INFINITY;
         int pi = -1;
         for (int j = 0; j < k; ++j) {
@@ -159,22 +167,33 @@ __global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict
                 const bool after_prev = (v < pv) || (v == pv && e > pi);
                 if (after_prev && (best < 0 || v > bv)) { best = e; bv = v; }
             };
-            int e = 0;
-            for (; e + 8 <= E; e += 8) {        // eight independent LDS reads in flight per step
+            int e = sub;
+            for (; e + 7 * L < E; e += 8 * L) {     // eight independent LDS reads in flight per step
                 float v[8];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) v[q] = row[e + q];
+                for (int q = 0; q < 8; ++q) v[q] = row[e + q * L];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) consider(e + q, v[q]);
+                for (int q = 0; q < 8; ++q) consider(e + q * L, v[q]);
             }
-            for (; e < E; ++e) consider(e, row[e]);
+            for (; e < E; e += L) consider(e, row[e]);
+            for (int mk = 1; mk < L; mk <<= 1) {    // the token's lanes agree on (value desc, index asc)
+                const float ov = __shfl_xor(bv, mk, kWave);
+                const int oi = __shfl_xor(best, mk, kWave);
+                if (oi >= 0 && (best < 0 || ov > bv || (ov == bv && oi < best))) { best = oi; bv = ov; }
+            }
             if (best < 0) best = (pi + 1 < E) ? pi + 1 : E - 1;   // unreachable for k <= E; keeps indices in range
-            sel[j] = best;
-            topk_idx[(size_t)t * k + j] = best;
             pv = bv;
             pi = best;
-            atomicOr(&s_mask[best * NW + wave], 1ull << lane);
+            if (sub == 0) {
+                sel[j] = best;
+                topk_idx[(size_t)t * k + j] = best;
+                atomicOr(&s_mask[best * NW + tword], tbit);
+            }
         }
+    }
+    if (leader) {
+        const float *row = s_l + tok * stride;
+        const int *sel = s_sel + tok * k;
         // gates: w_j = exp(l_j - l_0) in fp64, denominator summed in j (or expert) order, one rounding to fp32.
         // The first KW weights stay in registers; w_0 = exp(0) = 1 needs no call.
         constexpr int KW = 8;
@@ -207,13 +226,13 @@ __global__ __launch_bounds__(256) void route_plan_kernel(const float *__restrict
         for (int w = 0; w < NW; ++w) c += __popcll(s_mask[e * NW + w]);
         p.block_counts[(size_t)b * E + e] = c;
     }
-    if (active) {
-        const unsigned long long below = (1ull << lane) - 1ull;
+    if (leader) {
+        const unsigned long long below = tbit - 1ull;
         for (int j = 0; j < k; ++j) {
-            const int e = s_sel[tid * k + j];
+            const int e = s_sel[tok * k + j];
             int r = 0;
-            for (int w = 0; w < wave; ++w) r += __popcll(s_mask[e * NW + w]);
-            r += __popcll(s_mask[e * NW + wave] & below);
+            for (int w = 0; w < tword; ++w) r += __popcll(s_mask[e * NW + w]);
+            r += __popcll(s_mask[e * NW + tword] & below);
             p.local_rank[(size_t)t * k + j] = r;    // rank inside the workgroup; the positions kernels finish it
         }
     }
