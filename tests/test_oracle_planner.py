@@ -106,3 +106,35 @@ def test_lookup_interpolates_and_clamps():
     assert P.lookup(c, 5) == 0.2 and P.lookup(c, 100) == 0.8
     assert P.lookup(c, 15) == pytest.approx(0.3) and P.lookup(c, 30) == pytest.approx(0.6)
     assert P.lookup(c, 20) == pytest.approx(0.4)
+
+
+def test_lookup_volumes_and_the_alltoall_bound_branch():
+    # efficiency curves that differ at every volume involved, so a lookup at the wrong volume shows
+    I, t, e, N = 64e6, 4, 2, 2
+    b1, b2, b3 = 10e9, 100e9, 1e12
+    r1 = [(1e6, 0.1), (1e9, 0.9)]
+    r2 = [(1e6, 0.2), (1e9, 0.8)]
+    r3 = [(1e6, 0.3), (1e9, 0.7)]
+
+    def lin(c, v):
+        (x0, y0), (x1, y1) = c
+        return y0 + (y1 - y0) * (v - x0) / (x1 - x0)
+
+    aa, ag, d2d = P.chunk_times(I, N, t, e, b1, r1, b2, r2, b3, r3)
+    assert aa == pytest.approx(I / (N * t) * 0.5 / (b1 * lin(r1, I / (N * t))), rel=1e-12)    # r1 at I/(N t)
+    assert ag == pytest.approx(I / N * 0.75 / (b2 * lin(r2, I / N)), rel=1e-12)                # r2 at I/N
+    assert d2d == pytest.approx(I / N / (b3 * lin(r3, I / N)), rel=1e-12)                      # r3 at I/N
+    assert P.t_o1(I, t, e, b1, r1, b2, r2) == pytest.approx(
+        I / t * 0.5 / (b1 * lin(r1, I / t)) + I * 0.75 / (b2 * lin(r2, I)), rel=1e-12)       # r1 at I/t, r2 at I
+    # slow AllToAll: the chunked pipelines are bound by it, the gather (and copy) of the last chunk trail behind
+    slow = 0.2e9
+    aa, ag, d2d = P.chunk_times(I, 4, t, e, slow, r1, b2, r2, b3, r3)
+    assert aa > ag + d2d
+    assert P.t_chunked(I, 4, t, e, slow, r1, b2, r2, b3, r3, o3=False) == pytest.approx(aa * 4 + ag + d2d, rel=1e-12)
+    assert P.t_chunked(I, 4, t, e, slow, r1, b2, r2, b3, r3, o3=True) == pytest.approx(aa * 4 + ag + d2d, rel=1e-12)
+    # fast AllToAll: the gather stage bounds; Algorithm 1 pays the copy per chunk, Algorithm 2 once
+    fast = 1e12
+    aa, ag, d2d = P.chunk_times(I, 4, t, e, fast, r1, b2, r2, b3, r3)
+    assert aa < ag
+    assert P.t_chunked(I, 4, t, e, fast, r1, b2, r2, b3, r3, o3=False) == pytest.approx(aa + 4 * (ag + d2d), rel=1e-12)
+    assert P.t_chunked(I, 4, t, e, fast, r1, b2, r2, b3, r3, o3=True) == pytest.approx(aa + 4 * ag + d2d, rel=1e-12)
