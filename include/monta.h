@@ -140,6 +140,14 @@ int monta_dispatch(const monta_cfg *cfg, const void *x, void *stage, const void 
 int monta_regather(const monta_cfg *cfg, const void *stage, void *final_, const void *ws, int slice,
                    void *stream);
 
+/* The gather as a pass of its own (the O2 order of section "Pipelining": AllGather first, D2D copy
+ * after it): the STAGE rows of slice `slice` (all if -1), one contiguous range, are copied unchanged
+ * into `gathered` [max_rows][H] -- what every TP rank of the group holds after the AllGather.
+ * monta_regather(cfg, gathered, final_, ...) is then the D2D copy.  monta_regather straight from
+ * STAGE fuses the two passes and moves half the bytes; this entry point exists to measure the
+ * two-pass order against it. */
+int monta_allgather(const monta_cfg *cfg, const void *stage, void *gathered, const void *ws, int slice, void *stream);
+
 /* The slice pipeline (the paper's multi-stream schedule, section "AllToAll
  * performance", Implementation): regather(j) runs after pack(j) and overlaps
  * pack(j+1); everything has finished, in stream order, when the call's work on
@@ -238,7 +246,8 @@ enum monta_kernel_id {
     MONTA_K_PLAN_PACK = 7,  /* plan + positions + pack of slice 0 in one grid */
     MONTA_K_UNREGATHER = 8,
     MONTA_K_UNREGATHER_COMBINE = 9, /* co-scheduled grid of the return pipeline */
-    MONTA_K_COUNT = 10
+    MONTA_K_ALLGATHER = 10,
+    MONTA_K_COUNT = 11
 };
 int monta_profile_enable(int on);
 int monta_profile_reset(void);

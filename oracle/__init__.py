@@ -133,6 +133,20 @@ def regather(stage: np.ndarray, pl: Plan, tp: int, S: int, final: np.ndarray | N
     return final
 
 
+def allgather(stage: np.ndarray, pl: Plan, tp: int, S: int, gathered: np.ndarray | None = None, slice_: int = -1,
+              fill: int = 0) -> np.ndarray:
+    """The gather as a pass of its own: the slice's STAGE range, unchanged, in a second buffer."""
+    stage = np.ascontiguousarray(stage)
+    H = stage.shape[1]
+    E = pl.counts.shape[0]
+    if gathered is None:
+        gathered = np.full((pl.R, H), fill, dtype=stage.dtype)
+    rc = _load().monta_oracle_allgather(tp, S, E, ctypes.c_int64(H * stage.itemsize), _p(pl.n), _p(pl.stage_off),
+                                        _p(stage), _p(gathered), slice_)
+    _check(rc, "allgather")
+    return gathered
+
+
 def combine(y: np.ndarray, gates: np.ndarray, pos_final: np.ndarray) -> np.ndarray:
     """y [R,H] float32 or uint16(bf16) -> out [T,H] of the same type."""
     y = np.ascontiguousarray(y)

@@ -295,6 +295,25 @@ int monta_oracle_combine(int64_t T, int H, int k, int dtype, const void *y,
     return ORACLE_OK;
 }
 
+/* The gather as a pass of its own (the O2 order of section "Pipelining": AllGather, then the D2D
+ * copy): after the gather every TP rank of the group holds the pieces of all tp ranks of the slice
+ * side by side, i.e. the slice's whole STAGE range, unchanged, in a second buffer.  The D2D copy
+ * (monta_oracle_regather) then runs from that buffer.  slice < 0: all slices. */
+int monta_oracle_allgather(int tp, int S, int E, int64_t row_bytes, const int32_t *n,
+                           const int32_t *stage_off, const void *stage, void *gathered, int slice)
+{
+    if (tp < 1 || S < 1 || E < 1 || row_bytes < 1 || slice >= S) return ORACLE_BAD_ARG;
+    const int64_t U = (int64_t)S * tp;
+    for (int64_t u = 0; u < U; ++u) {
+        if (slice >= 0 && u / tp != slice) continue;
+        int64_t rows = 0;
+        for (int e = 0; e < E; ++e) rows += n[u * E + e];
+        memcpy((char *)gathered + (int64_t)stage_off[u * E] * row_bytes,
+               (const char *)stage + (int64_t)stage_off[u * E] * row_bytes, (size_t)(rows * row_bytes));
+    }
+    return ORACLE_OK;
+}
+
 /* ------------------------------------------------- the second AllToAll, mirrored */
 
 /* Section "Pipelining": "The same method can be applied to the second AllToAll".  After the experts

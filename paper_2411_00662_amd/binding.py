@@ -17,9 +17,9 @@ LIB_PATH = os.path.join(_PKG, "libmonta.so")
 
 FP32, BF16 = 0, 1
 (K_ROUTE, K_POSITIONS, K_PACK, K_REGATHER, K_PACK_REGATHER, K_COMBINE, K_COPY, K_PLAN_PACK, K_UNREGATHER,
- K_UNREGATHER_COMBINE) = range(10)
+ K_UNREGATHER_COMBINE, K_ALLGATHER) = range(11)
 KERNEL_NAMES = ["route_plan", "positions", "pack", "regather", "pack_regather", "combine", "copy", "plan_pack",
-                "unregather", "unregather_combine"]
+                "unregather", "unregather_combine", "allgather"]
 
 
 class MontaError(RuntimeError):
@@ -69,7 +69,7 @@ class monta_plan_out(ctypes.Structure):
 # every symbol include/monta.h declares
 EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "monta_route", "monta_dispatch",
            "monta_regather", "monta_dispatch_regather", "monta_route_dispatch_regather", "monta_combine", "monta_unregather", "monta_combine_staged",
-           "monta_unregather_combine", "monta_set_pipeline_mode",
+           "monta_unregather_combine", "monta_allgather", "monta_set_pipeline_mode",
            "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
            "monta_profile_read", "monta_plan_chunk_times", "monta_plan_strategy", "monta_strerror",
            "monta_last_hip_error"]
@@ -96,6 +96,7 @@ def lib() -> ctypes.CDLL:
         L.monta_combine.argtypes = [cfgp, vp, vp, vp, vp, vp]
         L.monta_route_dispatch_regather.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.monta_unregather.argtypes = [cfgp, vp, vp, vp, i32, vp]
+        L.monta_allgather.argtypes = [cfgp, vp, vp, vp, i32, vp]
         L.monta_combine_staged.argtypes = [cfgp, vp, vp, vp, vp, i32, vp]
         L.monta_unregather_combine.argtypes = [cfgp, vp, vp, vp, vp, vp, vp]
         L.monta_set_pipeline_mode.argtypes = [i32]
@@ -234,6 +235,14 @@ def monta_combine(cfg, y, gates, out, ws, stream=None):
     _check(lib().monta_combine(ctypes.byref(cfg), _ptr(y, L.max_rows * row, "y"),
                                _ptr(gates, cfg.tokens * cfg.top_k * 4, "gates"), _ptr(out, cfg.tokens * row, "out"),
                                _ptr(ws, L.ws_bytes, "ws"), _stream(stream)), "monta_combine")
+
+
+def monta_allgather(cfg, stage, gathered, ws, slice=-1, stream=None):
+    L = monta_ws_layout_query(cfg)
+    row = cfg.hidden * _bpe(cfg)
+    _check(lib().monta_allgather(ctypes.byref(cfg), _ptr(stage, L.max_rows * row, "stage"),
+                                 _ptr(gathered, L.max_rows * row, "gathered"), _ptr(ws, L.ws_bytes, "ws"), int(slice),
+                                 _stream(stream)), "monta_allgather")
 
 
 def monta_unregather(cfg, y, y_stage, ws, slice=-1, stream=None):

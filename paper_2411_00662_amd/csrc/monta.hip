@@ -627,6 +627,31 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
     return MONTA_OK;
 }
 
+int monta_allgather(const monta_cfg *cfg, const void *stage, void *gathered, const void *ws, int slice, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (slice < -1 || slice >= cfg->slices) return MONTA_ERR_INVALID;
+    if ((rc = check_act_ptrs(stage, gathered))) return rc;
+    if (stage == gathered) return MONTA_ERR_INVALID;
+    if ((rc = check_ws(ws))) return rc;
+    const Shape &s = g.s;
+    const PlanPtrs p = plan_ptrs(g, ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int u0 = slice < 0 ? 0 : slice * s.tp;
+    const int u1 = slice < 0 ? s.U : (slice + 1) * s.tp;
+    const int64_t vecs = slice_rows_bound(g, slice < 0 ? s.S : 1) * s.vpr;
+    int64_t wg = (vecs + (int64_t)kMoverThreads * kVecInFlight - 1) / ((int64_t)kMoverThreads * kVecInFlight);
+    if (wg < 1) wg = 1;
+    if (wg > 32768) wg = 32768;
+    ProfScope ps(MONTA_K_ALLGATHER, st);
+    hipLaunchKernelGGL(allgather_kernel, dim3((unsigned)wg), dim3(kMoverThreads), 0, st,
+                       static_cast<const u32x4 *>(stage), static_cast<u32x4 *>(gathered), p, s, u0, u1);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
 // mirrored return path -------------------------------------------------------------------------
 
 int monta_unregather(const monta_cfg *cfg, const void *y, void *y_stage, const void *ws, int slice, void *stream)

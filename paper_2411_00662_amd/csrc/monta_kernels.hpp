@@ -921,6 +921,29 @@ __global__ __launch_bounds__(kMoverThreads) void combine_kernel(const u32x4 *__r
     });
 }
 
+// The gather as a pass of its own: the STAGE rows of units [u0, u1) (one contiguous range, read from the
+// device table) copied unchanged into a second buffer.
+__global__ __launch_bounds__(kMoverThreads) void allgather_kernel(const u32x4 *__restrict__ stage,
+                                                                  u32x4 *__restrict__ gathered, PlanPtrs p, Shape s,
+                                                                  int u0, int u1)
+{
+    int r0 = p.unit_rows[u0], r1 = p.unit_rows[u1];
+    if (r0 < 0) r0 = 0;
+    if (r1 > s.max_rows) r1 = s.max_rows;
+    if (r1 <= r0) return;
+    const size_t first = (size_t)r0 * s.vpr, nvec = (size_t)(r1 - r0) * s.vpr;
+    const size_t stride = (size_t)gridDim.x * kMoverThreads * kVecInFlight;
+    for (size_t base = (size_t)blockIdx.x * kMoverThreads * kVecInFlight + threadIdx.x; base < nvec; base += stride) {
+        u32x4 val[kVecInFlight];
+#pragma unroll
+        for (int q = 0; q < kVecInFlight; ++q)
+            if (base + (size_t)q * kMoverThreads < nvec) val[q] = ld16<true>(stage + first + base + (size_t)q * kMoverThreads);
+#pragma unroll
+        for (int q = 0; q < kVecInFlight; ++q)
+            if (base + (size_t)q * kMoverThreads < nvec) st16<false>(gathered + first + base + (size_t)q * kMoverThreads, val[q]);
+    }
+}
+
 // ---- the second AllToAll, mirrored: y (FINAL layout) -> unit-major layout -> token order, slice by slice
 
 __global__ __launch_bounds__(kMoverThreads) void unregather_kernel(const u32x4 *__restrict__ y,

@@ -101,6 +101,9 @@ def test_null_and_misaligned_pointers_fail_before_any_gpu_work():
     assert lib.monta_combine(c, fake, 0, 2 * fake, fake, 0) == -3
     assert lib.monta_combine(c, fake, fake, fake, fake, 0) == -1
     assert lib.monta_combine(c, fake, fake, 2 * fake + 4, fake, 0) == -5
+    assert lib.monta_allgather(c, fake, fake, fake, 0, 0) == -1
+    assert lib.monta_allgather(c, fake, 2 * fake, 0, 0, 0) == -3
+    assert lib.monta_allgather(c, fake, 2 * fake, fake, 4, 0) == -1
     assert lib.monta_unregather(c, fake, fake, fake, 0, 0) == -1
     assert lib.monta_unregather(c, fake, 2 * fake, fake, 9, 0) == -1
     assert lib.monta_unregather(c, 0, 2 * fake, fake, 0, 0) == -3

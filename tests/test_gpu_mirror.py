@@ -111,3 +111,35 @@ def test_identity_experts_return_the_send_buffer(m):
     R = m.read_tables(cfg, b.ws)["R"]
     assert 0 < R < w.tokens * w.top_k
     assert torch.equal(ys[:R].view(torch.int16), b.stage[:R].view(torch.int16))
+
+
+def test_two_pass_gather_then_copy(m):
+    """monta_allgather + monta_regather from the gathered buffer equals the fused regather, slice by slice."""
+    import torch
+    from paper_2411_00662_amd import buffers as bufs
+    for w in (Workload("g1", 1320, 264, BF16, 6, 3, 3, 5, 4, 0.7, zipf_s=0.8), workloads.CONFIGS["mixtral"]):
+        print(f"two-pass {w.name}", flush=True)
+        logits, x = workloads.make_inputs(w, seed=4)
+        ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor)
+        R = ref.plan.R
+        cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm)
+        b = m.alloc_buffers(cfg, logits, x, canary=0xA5)
+        gathered = torch.empty_like(b.stage)
+        gathered.view(torch.uint8).fill_(0xA5)
+        m.monta_route(cfg, b.logits, b.topk_idx, b.gates, b.ws)
+        m.monta_dispatch(cfg, b.x, b.stage, b.ws, -1)
+        for j in reversed(range(w.slices)):
+            m.monta_allgather(cfg, b.stage, gathered, b.ws, j)
+            m.monta_regather(cfg, gathered, b.final, b.ws, j)
+        torch.cuda.synchronize()
+        gh = bufs.to_host_act(cfg, gathered)
+        np.testing.assert_array_equal(gh[:R], oracle.allgather(ref.stage, ref.plan, w.tp, w.slices))
+        assert (gh[R:].view(np.uint8) == 0xA5).all()
+        fh = bufs.to_host_act(cfg, b.final)
+        np.testing.assert_array_equal(fh[:R], ref.final)
+        assert (fh[R:].view(np.uint8) == 0xA5).all()
+        g2 = torch.zeros_like(b.stage)
+        m.monta_allgather(cfg, b.stage, g2, b.ws, -1)
+        torch.cuda.synchronize()
+        assert torch.equal(g2[:R].view(torch.int16 if w.dtype == BF16 else torch.int32),
+                           b.stage[:R].view(torch.int16 if w.dtype == BF16 else torch.int32))

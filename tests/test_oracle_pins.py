@@ -455,6 +455,24 @@ def test_fully_dropped_token_gives_zero_row_and_gates_not_renormalised():
     assert (r2.out[3:] == 0).all()
 
 
+def test_two_pass_gather_then_copy_equals_the_fused_pass():
+    w = Workload("t", 180, 8, FP32, 5, 2, 5, 3, 4, 0.8)
+    logits, x = workloads.make_inputs(w, seed=21)
+    logits[:, 1] += 1.0
+    r = oracle.forward(logits, x, k=2, ep=5, tp=3, S=4, cf=w.capacity_factor)
+    g = np.full_like(r.stage, 3)
+    for j in (3, 1, 0, 2):
+        before = g.copy()
+        oracle.allgather(r.stage, r.plan, 3, 4, gathered=g, slice_=j)
+        a, b = r.plan.stage_off[j * 3, 0], (r.plan.stage_off[(j + 1) * 3, 0] if j < 3 else r.plan.R)
+        np.testing.assert_array_equal(g[a:b], r.stage[a:b])          # exactly the slice's contiguous range
+        np.testing.assert_array_equal(g[:a], before[:a])
+        np.testing.assert_array_equal(g[b:], before[b:])
+    np.testing.assert_array_equal(g, r.stage)
+    np.testing.assert_array_equal(oracle.regather(g, r.plan, 3, 4), r.final)
+    np.testing.assert_array_equal(oracle.allgather(r.stage, r.plan, 3, 4), r.stage)
+
+
 # ------------------------------------------------------- mirrored return path
 
 @pytest.mark.parametrize("dtype", [FP32, BF16])
