@@ -71,7 +71,8 @@ def route(logits: np.ndarray, k: int, renorm: int = 1):
 @dataclass
 class Plan:
     C: int
-    R: int
+    R: int                  # kept pairs = STAGE rows
+    final_rows: int         # rows of FINAL: R (compact) or E*C (padded)
     alive: int
     counts: np.ndarray      # [E]
     kept: np.ndarray        # [E]
@@ -84,7 +85,7 @@ class Plan:
     send_rows: np.ndarray   # [U,ep]
 
 
-def plan(topk_idx: np.ndarray, E: int, ep: int, tp: int, S: int, cf: float) -> Plan:
+def plan(topk_idx: np.ndarray, E: int, ep: int, tp: int, S: int, cf: float, padded: int = 0) -> Plan:
     topk_idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
     T, k = topk_idx.shape
     U = S * tp
@@ -98,12 +99,14 @@ def plan(topk_idx: np.ndarray, E: int, ep: int, tp: int, S: int, cf: float) -> P
     pos_stage = np.empty((T, k), np.int32)
     send_rows = np.empty((U, ep), np.int32)
     alive = ctypes.c_int64(0)
-    rc = _load().monta_oracle_plan(ctypes.c_int64(T), E, k, ep, tp, S, ctypes.c_double(cf), _p(topk_idx),
+    kept_rows = ctypes.c_int64(0)
+    rc = _load().monta_oracle_plan(ctypes.c_int64(T), E, k, ep, tp, S, ctypes.c_double(cf), int(padded),
+                                   ctypes.byref(kept_rows), _p(topk_idx),
                                    _p(counts), _p(kept), _p(offsets), _p(pos_final), _p(n), _p(stage_off),
                                    _p(unit_base), _p(pos_stage), _p(send_rows), ctypes.byref(alive))
     _check(rc, "plan")
-    return Plan(capacity(T, E, k, cf), int(offsets[E]), int(alive.value), counts, kept, offsets, pos_final,
-                n, stage_off, unit_base, pos_stage, send_rows)
+    return Plan(capacity(T, E, k, cf), int(kept_rows.value), int(offsets[E]), int(alive.value), counts, kept, offsets,
+                pos_final, n, stage_off, unit_base, pos_stage, send_rows)
 
 
 def pack(x: np.ndarray, pl: Plan, tp: int, S: int, stage: np.ndarray | None = None, slice_: int = -1,
@@ -126,7 +129,7 @@ def regather(stage: np.ndarray, pl: Plan, tp: int, S: int, final: np.ndarray | N
     H = stage.shape[1]
     E = pl.counts.shape[0]
     if final is None:
-        final = np.full((pl.R, H), fill, dtype=stage.dtype)
+        final = np.full((pl.final_rows, H), fill, dtype=stage.dtype)
     rc = _load().monta_oracle_regather(tp, S, E, ctypes.c_int64(H * stage.itemsize), _p(pl.n), _p(pl.stage_off),
                                        _p(pl.unit_base), _p(stage), _p(final), slice_)
     _check(rc, "regather")
@@ -145,6 +148,14 @@ def allgather(stage: np.ndarray, pl: Plan, tp: int, S: int, gathered: np.ndarray
                                         _p(stage), _p(gathered), slice_)
     _check(rc, "allgather")
     return gathered
+
+
+def pad(final: np.ndarray, pl: Plan) -> np.ndarray:
+    """Zero-fills the padding rows of the capacity-padded layout (no-op for the compact layout)."""
+    E = pl.counts.shape[0]
+    rc = _load().monta_oracle_pad(E, ctypes.c_int64(final.shape[1] * final.itemsize), _p(pl.kept), _p(pl.offsets), _p(final))
+    _check(rc, "pad")
+    return final
 
 
 def combine(y: np.ndarray, gates: np.ndarray, pos_final: np.ndarray) -> np.ndarray:
@@ -227,12 +238,14 @@ class Result:
     out: np.ndarray
 
 
-def forward(logits, x, *, k, ep, tp, S, cf, renorm=1) -> Result:
+def forward(logits, x, *, k, ep, tp, S, cf, renorm=1, padded=0, fill=0) -> Result:
     """The whole path with identity experts (expert output = FINAL)."""
     E = logits.shape[1]
     idx, gates = route(logits, k, renorm)
-    pl = plan(idx, E, ep, tp, S, cf)
+    pl = plan(idx, E, ep, tp, S, cf, padded)
     stage = pack(x, pl, tp, S)
-    final = regather(stage, pl, tp, S)
+    final = regather(stage, pl, tp, S, fill=fill)
+    if padded:
+        pad(final, pl)
     out = combine(final, gates, pl.pos_final)
     return Result(idx, gates, pl, stage, final, out)

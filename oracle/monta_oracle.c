@@ -120,8 +120,13 @@ int64_t monta_oracle_capacity(int64_t T, int E, int k, double cf)
  *   pos_stage[T*k]   row of pair in STAGE, -1 if dropped
  *   send_rows[U*ep]  rows unit u sends to EP rank d (experts d*E/ep .. (d+1)*E/ep - 1)
  *   *alive           tokens with at least one kept pair (int64)
+ *
+ * padded != 0 selects the capacity-padded layout [E][C][H] of FINAL (the dispatch tensor of
+ * capacity-based MoE layers): expert e owns rows [e*C, (e+1)*C), its kept rows come first, the rest is
+ * padding.  Then offsets[e] = e*C and offsets[E] = E*C; the number of kept pairs is returned in *R.
+ * STAGE is compact in both layouts.
  */
-int monta_oracle_plan(int64_t T, int E, int k, int ep, int tp, int S, double cf,
+int monta_oracle_plan(int64_t T, int E, int k, int ep, int tp, int S, double cf, int padded, int64_t *R,
                       const int32_t *topk_idx, int32_t *counts, int32_t *kept,
                       int32_t *offsets, int32_t *pos_final, int32_t *n,
                       int32_t *stage_off, int32_t *unit_base, int32_t *pos_stage,
@@ -147,10 +152,13 @@ int monta_oracle_plan(int64_t T, int E, int k, int ep, int tp, int S, double cf,
             rank[t * k + j] = counts[e]++;
         }
     offsets[0] = 0;
+    int64_t rows = 0;
     for (int e = 0; e < E; ++e) {
         kept[e] = counts[e] < C ? counts[e] : (int32_t)C;
-        offsets[e + 1] = offsets[e] + kept[e];
+        rows += kept[e];
+        offsets[e + 1] = padded ? (int32_t)((e + 1) * C) : offsets[e] + kept[e];
     }
+    *R = rows;
     for (int64_t i = 0; i < U * E; ++i) n[i] = 0;
     int64_t live = 0;
     for (int64_t t = 0; t < T; ++t) {
@@ -223,6 +231,17 @@ int monta_oracle_pack(int64_t T, int k, int tp, int S, int64_t row_bytes, const 
 /* Intra-node gather + D2D copy "to the corresponding positions based on index
  * offsets" (paragraph "AllGather and D2D copy Pipelining"): every (unit, expert)
  * block of STAGE goes to its place in the expert-major FINAL buffer. */
+/* The padded layout's padding rows [offsets[e] + kept[e], offsets[e+1]) are zero-filled. */
+int monta_oracle_pad(int E, int64_t row_bytes, const int32_t *kept, const int32_t *offsets, void *final_)
+{
+    if (E < 1 || row_bytes < 1) return ORACLE_BAD_ARG;
+    for (int e = 0; e < E; ++e) {
+        const int64_t a = (int64_t)offsets[e] + kept[e], b = offsets[e + 1];
+        if (b > a) memset((char *)final_ + a * row_bytes, 0, (size_t)((b - a) * row_bytes));
+    }
+    return ORACLE_OK;
+}
+
 int monta_oracle_regather(int tp, int S, int E, int64_t row_bytes, const int32_t *n,
                           const int32_t *stage_off, const int32_t *unit_base,
                           const void *stage, void *final_, int slice)

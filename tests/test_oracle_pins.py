@@ -473,6 +473,35 @@ def test_two_pass_gather_then_copy_equals_the_fused_pass():
     np.testing.assert_array_equal(oracle.allgather(r.stage, r.plan, 3, 4), r.stage)
 
 
+@pytest.mark.parametrize("dtype", [FP32, BF16])
+def test_padded_layout_is_the_capacity_tensor(dtype):
+    w = Workload("t", 200, 16, dtype, 5, 2, 5, 2, 2, 0.8)
+    logits, x = workloads.make_inputs(w, seed=31)
+    logits[:, 0] += 1.5
+    comp = oracle.forward(logits, x, k=2, ep=5, tp=2, S=2, cf=w.capacity_factor)
+    padd = oracle.forward(logits, x, k=2, ep=5, tp=2, S=2, cf=w.capacity_factor, padded=1, fill=7)
+    C, E = comp.plan.C, 5
+    assert padd.plan.R == comp.plan.R and padd.plan.final_rows == E * C and padd.final.shape[0] == E * C
+    assert list(padd.plan.offsets) == [e * C for e in range(E + 1)]
+    cube = padd.final.reshape(E, C, w.hidden)
+    for e in range(E):
+        n_e = comp.plan.kept[e]
+        np.testing.assert_array_equal(cube[e, :n_e], comp.final[comp.plan.offsets[e]:comp.plan.offsets[e + 1]])
+        assert (cube[e, n_e:] == 0).all()                       # padding is zero-filled, not left at the fill value
+    assert (comp.plan.kept < C).any() and (comp.plan.kept == C).any()
+    # positions differ only by the segment base; STAGE is the same compact buffer; the result is the same
+    m = comp.plan.pos_final >= 0
+    e_of = comp.topk_idx[m]
+    np.testing.assert_array_equal(padd.plan.pos_final[m] - e_of * C, comp.plan.pos_final[m] - comp.plan.offsets[e_of])
+    np.testing.assert_array_equal(padd.plan.pos_final[~m], -1)
+    np.testing.assert_array_equal(padd.stage, comp.stage)
+    np.testing.assert_array_equal(padd.plan.pos_stage, comp.plan.pos_stage)
+    np.testing.assert_array_equal(padd.out, comp.out)
+    np.testing.assert_array_equal(padd.plan.unit_base - np.arange(E)[None, :] * C, comp.plan.unit_base - comp.plan.offsets[None, :E])
+    # the return path works on it unchanged
+    np.testing.assert_array_equal(oracle.unregather(padd.final, padd.plan, 2, 2), padd.stage)
+
+
 # ------------------------------------------------------- mirrored return path
 
 @pytest.mark.parametrize("dtype", [FP32, BF16])
