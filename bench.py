@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--return-path", default="direct", choices=["direct", "mirror"],
                     help="direct: combine reads the expert output in FINAL layout (the headline path); mirror: the "
                          "second AllToAll mirrored (unregather + staged combine pipeline), 2R more rows moved")
+    ap.add_argument("--padded", type=int, default=0, help="1: capacity-padded [E][C][H] layout of FINAL (zero-filled padding)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     args = ap.parse_args()
@@ -88,11 +89,14 @@ def main():
     w = workloads.CONFIGS[args.config]
     if args.slices:
         w = w.with_(slices=args.slices)
+    if args.padded:
+        w = w.with_(padded=1)
     if args.mode >= 0:
         m.monta_set_pipeline_mode(args.mode)
     mode = m.monta_get_pipeline_mode()
     logits, x = workloads.make_inputs(w)
-    cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm)
+    cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm,
+                     w.padded)
     b = m.alloc_buffers(cfg, logits, x)
 
     stream = torch.cuda.Stream()          # default priority; the whole step is enqueued on it
@@ -144,6 +148,11 @@ def main():
 
     tabs = m.read_tables(cfg, b.ws)
     ab = algorithmic_bytes(w, tabs)
+    if w.padded:
+        pad_bytes = (tabs["final_rows"] - ab["R"]) * ab["row"]      # zero-filled by the regather of slice 0
+        ab["total"] += pad_bytes
+        ab["regather_s"][0] += pad_bytes
+        ab["regather"] += pad_bytes
     if mirror:
         ab["total"] += 2 * ab["R"] * ab["row"]
         ab["unregather_s"] = ab["regather_s"]
@@ -236,7 +245,8 @@ def main():
         budget = 12.0
         while reps < 20 and spent < budget:
             c0 = time.perf_counter()
-            oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm)
+            oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm,
+                           padded=w.padded)
             spent += time.perf_counter() - c0
             reps += 1
         cpu = {"value": round(w.tokens * reps / spent, 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
@@ -251,7 +261,7 @@ def main():
         "config": {"workload": w.name, "tokens": w.tokens, "hidden": w.hidden, "experts": w.experts,
                    "top_k": w.top_k, "ep": w.ep, "tp": w.tp, "slices": w.slices,
                    "capacity_factor": w.capacity_factor, "kept_rows": ab["R"], "alive_tokens": ab["alive"],
-                   "pipeline_mode": mode, "hip_graph": use_graph, "return_path": args.return_path,
+                   "pipeline_mode": mode, "hip_graph": use_graph, "return_path": args.return_path, "padded": w.padded,
                    "parallelism": "1 GPU, virtual ep/tp"},
         "effective_GBps": round(eff_gbps, 1), "pct_of_hbm_peak": round(100 * eff_gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_bytes_per_step": int(ab["total"]),

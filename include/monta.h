@@ -75,22 +75,26 @@ typedef struct monta_cfg {
     float capacity_factor;   /* 0: nothing is dropped; else C = min(T, ceil(cf*T*k/E)) per expert,
                                 global over all tokens, lowest token indices survive            */
     int32_t renorm;          /* 1: gates renormalised over the k winners; 0: softmax over all E */
+    int32_t padded;          /* 0: compact FINAL (expert segments back to back, R rows);
+                                1: capacity-padded FINAL [E][C][H]: expert e owns rows [e*C, (e+1)*C), kept rows
+                                   first, the padding zero-filled by the regather of slice 0 (or of all slices).
+                                   STAGE stays compact.  With capacity_factor = 0, C = T. */
 } monta_cfg;
 
 /* Where the plan tables live inside the caller's workspace (byte offsets from
  * `ws`; every table is int32, row-major).  Filled by monta_ws_layout_query(). */
 typedef struct monta_ws_layout {
     int64_t ws_bytes;        /* size the caller must allocate (256-byte aligned base)           */
-    int64_t max_rows;        /* rows STAGE / FINAL / expert output must hold: min(T*k, E*C)     */
+    int64_t max_rows;        /* rows STAGE / FINAL / expert output must hold: min(T*k, E*C), or E*C if padded */
     int64_t capacity;        /* C                                                               */
     int32_t units;           /* U                                                               */
     int32_t tokens_per_unit; /* Tu                                                              */
     int32_t block_tokens;    /* tokens routed per workgroup (internal granularity)             */
     int32_t num_blocks;      /* workgroups of the route kernel                                  */
-    int64_t off_meta;        /* [16]: [0] R  [1] tokens with >= 1 kept pair  [2] C  (rest internal) */
+    int64_t off_meta;        /* [16]: [0] R (kept pairs)  [1] tokens with >= 1 kept pair  [2] C  [4] rows of FINAL */
     int64_t off_counts;      /* [E]     pairs that chose expert e                               */
     int64_t off_kept;        /* [E]     min(counts, C)                                          */
-    int64_t off_offsets;     /* [E+1]   exclusive scan of kept; offsets[E] = R                  */
+    int64_t off_offsets;     /* [E+1]   first FINAL row of expert e (exclusive scan of kept, or e*C if padded) */
     int64_t off_n;           /* [U][E]  kept pairs of expert e with token in unit u             */
     int64_t off_stage_off;   /* [U][E]  first STAGE row of block (u,e)                          */
     int64_t off_unit_base;   /* [U][E]  first FINAL row of block (u,e)                          */
@@ -103,6 +107,7 @@ typedef struct monta_ws_layout {
     int64_t off_block_base;  /* [num_blocks][E] internal                                        */
     int64_t off_local_rank;  /* [T][k] internal: rank of a pair inside its route workgroup      */
     int64_t off_final_order; /* [max_rows] internal: STAGE rows of each slice listed expert by expert */
+    int64_t off_kept_prefix; /* [E+1] internal: exclusive scan of kept (= offsets when compact)    */
 } monta_ws_layout;
 
 /* Host only.  Validates cfg and reports the workspace size and the row capacity

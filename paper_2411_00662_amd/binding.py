@@ -32,7 +32,7 @@ class monta_cfg(ctypes.Structure):
     _fields_ = [("tokens", ctypes.c_int64), ("hidden", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("experts", ctypes.c_int32), ("top_k", ctypes.c_int32), ("ep", ctypes.c_int32),
                 ("tp", ctypes.c_int32), ("slices", ctypes.c_int32), ("capacity_factor", ctypes.c_float),
-                ("renorm", ctypes.c_int32)]
+                ("renorm", ctypes.c_int32), ("padded", ctypes.c_int32)]
 
 
 class monta_ws_layout(ctypes.Structure):
@@ -45,7 +45,8 @@ class monta_ws_layout(ctypes.Structure):
                 ("off_unit_rows", ctypes.c_int64), ("off_pos_final", ctypes.c_int64),
                 ("off_pos_stage", ctypes.c_int64), ("off_row_map", ctypes.c_int64),
                 ("off_block_counts", ctypes.c_int64), ("off_block_base", ctypes.c_int64),
-                ("off_local_rank", ctypes.c_int64), ("off_final_order", ctypes.c_int64)]
+                ("off_local_rank", ctypes.c_int64), ("off_final_order", ctypes.c_int64),
+                ("off_kept_prefix", ctypes.c_int64)]
 
 
 class monta_curve(ctypes.Structure):
@@ -137,9 +138,9 @@ def _check(code: int, what: str):
         raise MontaError(code, what, detail)
 
 
-def make_cfg(tokens, hidden, dtype, experts, top_k, ep, tp, slices, capacity_factor=0.0, renorm=1) -> monta_cfg:
+def make_cfg(tokens, hidden, dtype, experts, top_k, ep, tp, slices, capacity_factor=0.0, renorm=1, padded=0) -> monta_cfg:
     return monta_cfg(int(tokens), int(hidden), int(dtype), int(experts), int(top_k), int(ep), int(tp), int(slices),
-                     float(capacity_factor), int(renorm))
+                     float(capacity_factor), int(renorm), int(padded))
 
 
 def _bpe(cfg) -> int:

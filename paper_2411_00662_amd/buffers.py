@@ -98,6 +98,8 @@ def read_tables(cfg, ws) -> dict:
         cnt = int(np.prod(shape))
         off = getattr(L, off_name)
         out[name] = host[off:off + 4 * cnt].view(np.int32).reshape(shape).copy()
+    out["kept_prefix"] = host[L.off_kept_prefix:L.off_kept_prefix + 4 * (cfg.experts + 1)].view(np.int32).copy()
+    out["final_rows"] = int(out["meta"][4])
     out["R"] = int(out["meta"][0])
     out["alive"] = int(out["meta"][1])
     out["C"] = int(out["meta"][2])

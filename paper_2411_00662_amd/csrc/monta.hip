@@ -81,6 +81,7 @@ int validate(const monta_cfg *c, Geometry *g)
         return MONTA_ERR_INVALID;
     if (c->dtype != MONTA_FP32 && c->dtype != MONTA_BF16) return MONTA_ERR_INVALID;
     if (c->renorm != 0 && c->renorm != 1) return MONTA_ERR_INVALID;
+    if (c->padded != 0 && c->padded != 1) return MONTA_ERR_INVALID;
     if (c->top_k > c->experts) return MONTA_ERR_INVALID;
     if (c->experts % c->ep != 0) return MONTA_ERR_INVALID;
     if (!(c->capacity_factor >= 0.f) || !std::isfinite(c->capacity_factor)) return MONTA_ERR_INVALID;
@@ -130,7 +131,9 @@ int validate(const monta_cfg *c, Geometry *g)
     s.rl = rl;
     g->route_threads = TB * rl < kWave ? kWave : TB * rl;
     const int64_t tk = c->tokens * (int64_t)c->top_k, ec = (int64_t)c->experts * s.C;
-    g->max_rows = tk < ec ? tk : ec;
+    if (c->padded && ec > 0x7fffffffLL) return MONTA_ERR_UNSUPPORTED;
+    s.padded = c->padded;
+    g->max_rows = c->padded ? ec : (tk < ec ? tk : ec);
     s.max_rows = (int32_t)g->max_rows;
     {
         // Measured on MI355X (256 MB memory-side cache): a producer's cacheable stores pay when the
@@ -177,6 +180,7 @@ void fill_layout(const Geometry &g, monta_ws_layout *L)
     L->off_block_base = take((int64_t)s.num_blocks * s.E);
     L->off_local_rank = take((int64_t)s.T * s.k);
     L->off_final_order = take(g.max_rows);
+    L->off_kept_prefix = take(s.E + 1);
     L->ws_bytes = off;
 }
 
@@ -203,6 +207,7 @@ PlanPtrs plan_ptrs(const Geometry &g, const void *ws)
     p.block_base = at(L.off_block_base);
     p.local_rank = at(L.off_local_rank);
     p.final_order = at(L.off_final_order);
+    p.kept_prefix = at(L.off_kept_prefix);
     return p;
 }
 

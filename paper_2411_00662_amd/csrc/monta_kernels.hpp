@@ -27,11 +27,11 @@ constexpr int kMoverThreads = MONTA_MOVER_THREADS;   // threads per workgroup of
 constexpr int kVecInFlight = MONTA_VEC_IN_FLIGHT;    // 16-byte loads issued by a lane before its first store
 
 // meta[] slots (int32)
-enum { META_R = 0, META_ALIVE = 1, META_C = 2, META_DONE = 3, META_SLOTS = 16 };
+enum { META_R = 0, META_ALIVE = 1, META_C = 2, META_DONE = 3, META_FINAL_ROWS = 4, META_SLOTS = 16 };
 
 struct PlanPtrs {
     int32_t *meta, *counts, *kept, *offsets, *n, *stage_off, *unit_base, *send_rows, *unit_rows;
-    int32_t *pos_final, *pos_stage, *row_map, *block_counts, *block_base, *local_rank, *final_order;
+    int32_t *pos_final, *pos_stage, *row_map, *block_counts, *block_base, *local_rank, *final_order, *kept_prefix;
 };
 
 struct Shape {
@@ -45,6 +45,7 @@ struct Shape {
     int32_t lpr;       // lanes cooperating on one row in the movers (power of two <= kMoverThreads)
     int32_t max_rows;  // rows STAGE / FINAL hold; every row index read from a table is checked against it
     int32_t cache;     // CachePolicy bits: which streams of the movers use non-temporal accesses
+    int32_t padded;    // 1: FINAL is [E][C][H] (expert e at row e*C), 0: compact
     int32_t rl;        // lanes that share one token in the route kernel (1, 2, 4 or 8)
     int32_t fast_plan; // 1: plan_positions_kernel rebuilds the scans per workgroup; 0: ticketed scan + positions_kernel
 };
@@ -273,15 +274,19 @@ __global__ __launch_bounds__(1024) void route_plan_kernel(const float *__restric
             const int kp = cnt < C ? cnt : C;
             const int incl = wave_inclusive_scan(kp, lane);
             if (e < E) {
+                const int off = s.padded ? e * C : carry + incl - kp;
                 p.counts[e] = cnt;
                 p.kept[e] = kp;
-                p.offsets[e] = carry + incl - kp;
-                s_off[e] = carry + incl - kp;
+                p.kept_prefix[e] = carry + incl - kp;
+                p.offsets[e] = off;
+                s_off[e] = off;
             }
             carry += __shfl(incl, kWave - 1, kWave);
         }
         if (lane == 0) {
-            p.offsets[E] = carry;
+            p.kept_prefix[E] = carry;
+            p.offsets[E] = s.padded ? E * C : carry;
+            p.meta[META_FINAL_ROWS] = s.padded ? E * C : carry;
             p.meta[META_R] = carry;
             p.meta[META_C] = C;
         }
@@ -368,6 +373,7 @@ struct BlockPlan {
     int pre[256];      // pairs of e in b's unit, in workgroups before b
     int total[256];    // counts[e]
     int off[256];      // offsets[e]: first FINAL row of expert e
+    int kpre[256];     // exclusive scan of the kept counts (= off when the layout is compact)
     int stage[256];    // stage_off[u][e]: first STAGE row of block (u, e)
     int sbefore[256];  // pairs of e in slices before b's slice
     int sin[256];      // pairs of e in b's slice
@@ -475,7 +481,8 @@ __device__ __forceinline__ void block_plan(BlockPlan &bp, int b, const PlanPtrs 
             const int incl_st = wave_inclusive_scan(nu, lane);
             const int incl_fo = wave_inclusive_scan(ns, lane);
             if (e < E) {
-                bp.off[e] = carry_off + incl_off - kp;
+                bp.kpre[e] = carry_off + incl_off - kp;
+                bp.off[e] = s.padded ? e * C : carry_off + incl_off - kp;
                 bp.stage[e] = base_u + carry_stage + incl_st - nu;
                 // expert-major listing of the slice: rows of earlier experts, then this expert's rows of earlier units
                 bp.forder[e] = base_s + carry_fo + incl_fo - ns + (lo - slo);
@@ -552,14 +559,17 @@ __device__ __forceinline__ void plan_positions_block(BlockPlan &bp, int b, const
             p.counts[e] = bp.total[e];
             p.kept[e] = bp.total[e] < C ? bp.total[e] : C;
             p.offsets[e] = bp.off[e];
+            p.kept_prefix[e] = bp.kpre[e];
         }
     }
     if (tid == 0) {
         if (ib == 0) p.unit_rows[u] = bp.unit_row0;
         if (b == 0) {
-            p.offsets[E] = bp.R;
+            p.offsets[E] = s.padded ? E * C : bp.R;
+            p.kept_prefix[E] = bp.R;
             p.unit_rows[s.U] = bp.R;
             p.meta[META_R] = bp.R;
+            p.meta[META_FINAL_ROWS] = s.padded ? E * C : bp.R;
             p.meta[META_C] = C;
         }
     }
@@ -691,6 +701,30 @@ __device__ __forceinline__ void regather_rows_t(u32x4 *stage, u32x4 *fin, const 
     }
 }
 
+// Capacity-padded layout: zero-fills the padding rows [e*C + kept[e], (e+1)*C) of every expert.  Padding row i
+// (0 <= i < E*C - R) belongs to the expert found by bisection over pad_before[e] = e*C - kept_prefix[e].
+__device__ __forceinline__ void pad_rows(u32x4 *__restrict__ fin, const PlanPtrs &p, const Shape &s, int wg, int nwg)
+{
+    const int lpr = s.lpr, vpr = s.vpr, E = s.E, C = s.C;
+    const int rows_per_wg = kMoverThreads / lpr;
+    const int sub = threadIdx.x / lpr, lane = threadIdx.x - sub * lpr;
+    int total = E * C - p.kept_prefix[E];
+    if (total > s.max_rows) total = s.max_rows;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (int i = wg * rows_per_wg + sub; i < total; i += nwg * rows_per_wg) {
+        int lo = 0, hi = E - 1;                      // largest e with pad_before[e] <= i
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (mid * C - p.kept_prefix[mid] <= i) lo = mid;
+            else hi = mid - 1;
+        }
+        const int row = lo * C + p.kept[lo] + (i - (lo * C - p.kept_prefix[lo]));
+        if ((unsigned)row >= (unsigned)s.max_rows || row >= (lo + 1) * C) continue;
+        u32x4 *dst = fin + (size_t)row * vpr;
+        for (int v = lane; v < vpr; v += lpr) st16<true>(dst + v, zero);
+    }
+}
+
 __device__ __forceinline__ void regather_rows(const u32x4 *__restrict__ stage, u32x4 *__restrict__ fin,
                                               const PlanPtrs &p, const Shape &s, int r0, int r1, int wg, int nwg)
 {
@@ -785,6 +819,7 @@ __global__ __launch_bounds__(kMoverThreads) void regather_kernel(const u32x4 *__
                                                                  int u0, int u1)
 {
     regather_rows(stage, fin, p, s, p.unit_rows[u0], p.unit_rows[u1], blockIdx.x, gridDim.x);
+    if (s.padded && u0 == 0) pad_rows(fin, p, s, blockIdx.x, gridDim.x);
 }
 
 // One grid, two jobs in disjoint workgroups: the first n_pack_wg workgroups pack
@@ -811,7 +846,10 @@ __global__ __launch_bounds__(kMoverThreads) void pack_regather_kernel(const u32x
     if (is_pack)
         pack_rows(x, stage, p.pos_stage, s, t0, nt, idx, n_pack_wg);
     else
+{
         regather_rows(stage, fin, p, s, p.unit_rows[u0], p.unit_rows[u1], idx, n_reg_wg);
+        if (s.padded && u0 == 0) pad_rows(fin, p, s, idx, n_reg_wg);
+    }
 }
 
 // ------------------------------------------------------------------ combine

@@ -29,9 +29,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_the_header_layout():
-    # int64 + 8 * int32 + float + int32 => 48 bytes; layout: 3 * int64 + 4 * int32 + 16 * int64
+    # int64 + 7 * int32 + float + 2 * int32 = 48 bytes; layout: 3 * int64 + 4 * int32 + 17 * int64
     assert ctypes.sizeof(B.monta_cfg) == 48
-    assert ctypes.sizeof(B.monta_ws_layout) == 3 * 8 + 4 * 4 + 16 * 8
+    assert ctypes.sizeof(B.monta_ws_layout) == 3 * 8 + 4 * 4 + 17 * 8
 
 
 def test_workspace_query_named_workloads():
@@ -41,6 +41,8 @@ def test_workspace_query_named_workloads():
     assert L.max_rows == 524288 and L.capacity == 10240 and L.units == 32 and L.tokens_per_unit == 2048
     L = m.monta_ws_layout_query(m.make_cfg(256, 128, m.FP32, 4, 2, 2, 2, 2, 0.0))
     assert L.max_rows == 512 and L.capacity == 256
+    L = m.monta_ws_layout_query(m.make_cfg(8192, 4096, m.BF16, 8, 2, 8, 1, 4, 2.0, padded=1))
+    assert L.max_rows == 8 * 4096           # padded: E*C rows even though only T*k = 16384 pairs exist
     # cf binds the row bound: E*C < T*k
     L = m.monta_ws_layout_query(m.make_cfg(1024, 64, m.BF16, 4, 2, 2, 1, 1, 0.5))
     assert L.capacity == 256 and L.max_rows == 1024
@@ -51,7 +53,7 @@ def test_workspace_query_named_workloads():
 
 @pytest.mark.parametrize("field,value,code", [
     ("tokens", 0, -1), ("hidden", 0, -1), ("experts", 0, -1), ("top_k", 0, -1), ("ep", 0, -1), ("tp", 0, -1),
-    ("slices", 0, -1), ("dtype", 2, -1), ("renorm", 2, -1),
+    ("slices", 0, -1), ("dtype", 2, -1), ("renorm", 2, -1), ("padded", 2, -1), ("padded", -1, -1),
     ("top_k", 9, -1),            # k > E
     ("ep", 3, -1),               # E % ep != 0
     ("slices", 3, -1),           # T % (S*tp) != 0

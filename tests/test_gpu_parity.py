@@ -37,7 +37,8 @@ def m():
 
 
 def cfg_of(m, w: Workload):
-    return m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm)
+    return m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm,
+                      w.padded)
 
 
 def run_gpu(m, w, logits, x, mode=1, how="pipeline", canary=0xA5, repeats=1, plan_mode=-1, cache=-1):
@@ -87,17 +88,19 @@ def canary_value(dtype, byte=0xA5):
 
 def check_against_oracle(w, logits, x, got, ref=None, canary=0xA5):
     if ref is None:
-        ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm)
+        ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm,
+                             padded=w.padded, fill=canary if canary is not None else 0)
     pl = ref.plan
     np.testing.assert_array_equal(got["topk_idx"], ref.topk_idx)
     g, gr = got["gates"].astype(np.float64), ref.gates.astype(np.float64)
     assert np.all(np.abs(g - gr) <= 1e-6 * np.abs(gr)), f"gates: max rel {np.max(np.abs(g - gr) / np.abs(gr))}"
-    assert got["R"] == pl.R and got["alive"] == pl.alive and got["C"] == pl.C
+    assert got["R"] == pl.R and got["alive"] == pl.alive and got["C"] == pl.C and got["final_rows"] == pl.final_rows
     for name in ["counts", "kept", "offsets", "n", "stage_off", "unit_base", "send_rows", "pos_final", "pos_stage"]:
         np.testing.assert_array_equal(got[name], getattr(pl, name), err_msg=name)
     U = w.slices * w.tp
     np.testing.assert_array_equal(got["unit_rows"][:U], pl.stage_off[:, 0])
     assert got["unit_rows"][U] == pl.R
+    np.testing.assert_array_equal(got["kept_prefix"], np.concatenate([[0], np.cumsum(pl.kept)]))
     # STAGE -> FINAL row map, from the oracle's two position tables
     rm = np.full(pl.R, -1, np.int32)
     live = pl.pos_stage >= 0
@@ -116,13 +119,13 @@ def check_against_oracle(w, logits, x, got, ref=None, canary=0xA5):
         assert np.array_equal(np.sort(fo[a:b_]), rows), "final_order is not a permutation of the slice's rows"
     assert np.array_equal(fo, expect_em) or np.array_equal(fo, np.arange(pl.R))
     # buffers: bit-exact below R, untouched above
-    for name, refbuf in (("stage_full", ref.stage), ("final_full", ref.final)):
+    for name, refbuf, rows in (("stage_full", ref.stage, pl.R), ("final_full", ref.final, pl.final_rows)):
         buf = got[name]
         assert buf.dtype == refbuf.dtype
-        np.testing.assert_array_equal(buf[:pl.R], refbuf, err_msg=name)
-        if canary is not None and buf.shape[0] > pl.R:
-            tail = buf[pl.R:]
-            assert (tail.view(np.uint8) == canary).all(), f"{name}: rows past R were written"
+        np.testing.assert_array_equal(buf[:rows], refbuf, err_msg=name)
+        if canary is not None and buf.shape[0] > rows:
+            tail = buf[rows:]
+            assert (tail.view(np.uint8) == canary).all(), f"{name}: rows past the end were written"
     check_combine(w, got["out"], ref.out, ref.final, ref.gates, pl.pos_final, got["gates"])
     return ref
 
@@ -460,3 +463,35 @@ def test_random_small_shapes(m):
         got = run_gpu(m, w, logits, x, mode=mode, how=how, plan_mode=plan_mode, cache=cache)
         check_against_oracle(w, logits, x, got)
         done += 1
+
+
+PADDED = [
+    Workload("p1", 330, 40, BF16, 5, 3, 5, 2, 3, 0.7, zipf_s=0.8, padded=1),
+    Workload("p2", 4096, 1028, FP32, 16, 4, 4, 2, 2, 0.3, zipf_s=0.8, padded=1),
+    Workload("p3", 1000, 264, BF16, 7, 7, 7, 5, 2, 0.5, renorm=0, zipf_s=0.8, padded=1),
+    Workload("p4", 600, 64, BF16, 8, 2, 4, 1, 1, 0.0, padded=1),                       # cf = 0: C = T, huge padding
+    Workload("p5", 4096, 8, BF16, 32, 2, 4, 64, 64, 0.9, zipf_s=0.8, padded=1),        # ticketed plan path
+    workloads.CONFIGS["mixtral"].with_(padded=1),
+    workloads.CONFIGS["longctx"].with_(padded=1, tokens=8192),
+]
+
+
+@pytest.mark.parametrize("w", PADDED, ids=lambda w: w.name + "-padded")
+def test_padded_layout(m, w):
+    """FINAL as the capacity tensor [E][C][H]: kept rows first in every expert segment, zero padding after them."""
+    logits, x = workloads.make_inputs(w, seed=7)
+    ref = None
+    for mode, how, plan_mode in ((1, "fused_call", -1), (0, "pipeline", -1), (2, "all", 0), (1, "slices_reversed", -1)):
+        _say(f"padded {w.name} mode={mode} how={how} plan_mode={plan_mode}")
+        got = run_gpu(m, w, logits, x, mode=mode, how=how, plan_mode=plan_mode)
+        ref = check_against_oracle(w, logits, x, got, ref)
+    C, E = ref.plan.C, w.experts
+    assert got["final_full"].shape[0] == E * C == ref.plan.final_rows
+    cube = got["final_full"].reshape(E, C, w.hidden)
+    for e in range(E):
+        assert (cube[e, ref.plan.kept[e]:] == 0).all()
+    # same result as the compact layout
+    wc = w.with_(padded=0)
+    gotc = run_gpu(m, wc, logits, x, mode=1, how="fused_call")
+    np.testing.assert_array_equal(gotc["out"], got["out"])
+    np.testing.assert_array_equal(gotc["stage_full"][:ref.plan.R], got["stage_full"][:ref.plan.R])

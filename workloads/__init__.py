@@ -40,6 +40,7 @@ class Workload:
     capacity_factor: float  # 0 => dropless
     renorm: int = 1        # gates renormalised over the k winners
     zipf_s: float = 0.0    # > 0 => add -s*ln(e+1) to the logits
+    padded: int = 0        # 1 => capacity-padded [E][C][H] layout of the expert-major buffer
     seed: int = 0
 
     def __post_init__(self):
