@@ -687,7 +687,9 @@ namespace {
 int launch_unregather_combine(const Geometry &g, const PlanPtrs &p, int dtype, const void *y, void *y_stage,
                               const float *gates, void *out, int u0, int u1, int t0, int nt, hipStream_t st)
 {
-    const Shape &s = g.s;
+    Shape s = g.s;
+    // the rows fetched back are read exactly once by the staged combine: stream them unless the caller set a policy
+    if (g_cache_policy.load() < 0) s.cache |= NT_COMB_LD;
     const int n_unreg = u0 < u1 ? regather_grid(s, slice_rows_bound(g, (u1 - u0) / s.tp)) : 0;
     const int n_comb = nt > 0 ? mover_grid(s, nt) : 0;
     if (n_unreg + n_comb == 0) return MONTA_OK;
