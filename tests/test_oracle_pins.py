@@ -186,6 +186,40 @@ def test_plan_equals_brute_force(T, E, k, ep, tp, S, cf):
         assert (pos_final < 0).any(), "case was meant to exercise drops"
 
 
+def test_plan_equals_brute_force_on_random_problems():
+    rng = np.random.default_rng(77)
+    for case in range(60):
+        E = int(rng.integers(1, 20))
+        k = int(rng.integers(1, min(E, 5) + 1))
+        ep = int(rng.choice([d for d in range(1, E + 1) if E % d == 0]))
+        tp, S = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        T = int(rng.integers(1, 30)) * tp * S
+        cf = float(np.float32(rng.choice([0.0, 0.2, 0.5, 1.0, 1.7])))
+        padded = int(rng.integers(0, 2))
+        logits = rng.standard_normal((T, E), dtype=np.float32)
+        if rng.integers(0, 2):
+            logits = np.round(logits)                     # plenty of ties
+        logits[:, 0] += np.float32(rng.choice([0.0, 1.0]))
+        idx, _ = oracle.route(logits, k)
+        for t in range(T):
+            assert list(idx[t]) == brute_topk(logits[t], k)
+        pl = oracle.plan(idx, E, ep, tp, S, cf, padded)
+        C = T if cf == 0 else min(T, math.ceil(cf * T * k / E))
+        lists, kept_lists, final_order, stage_order, pos_final, pos_stage = brute_plan(idx, E, ep, tp, S, C)
+        assert pl.C == C and pl.R == len(final_order), case
+        np.testing.assert_array_equal(pl.pos_stage, pos_stage)
+        if padded:
+            exp = -np.ones_like(pos_final)
+            for e in range(E):
+                for r, (t, j) in enumerate(kept_lists[e]):
+                    exp[t, j] = e * C + r
+            np.testing.assert_array_equal(pl.pos_final, exp)
+            assert pl.final_rows == E * C
+        else:
+            np.testing.assert_array_equal(pl.pos_final, pos_final)
+            assert pl.final_rows == pl.R
+
+
 def test_plan_dropless_is_numpy_stable_argsort():
     rng = np.random.default_rng(5)
     T, E, k = 512, 16, 4
