@@ -68,6 +68,20 @@ def route(logits: np.ndarray, k: int, renorm: int = 1):
     return idx, gates
 
 
+def gate(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """Gate projection: x [T,H], w [E,H] (float32, or uint16 bf16 bits) -> logits float32 [T,E]."""
+    x = np.ascontiguousarray(x)
+    w = np.ascontiguousarray(w)
+    if x.dtype != w.dtype or x.dtype not in (np.float32, np.uint16) or x.shape[1] != w.shape[1]:
+        raise ValueError("oracle gate: x and w must share dtype (float32 or uint16) and hidden size")
+    T, H = x.shape
+    E = w.shape[0]
+    logits = np.empty((T, E), np.float32)
+    rc = _load().monta_oracle_gate(ctypes.c_int64(T), H, E, 0 if x.dtype == np.float32 else 1, _p(x), _p(w), _p(logits))
+    _check(rc, "gate")
+    return logits
+
+
 @dataclass
 class Plan:
     C: int

@@ -89,6 +89,37 @@ int monta_oracle_route(int64_t T, int E, int k, int renorm, const float *logits,
     return ORACLE_OK;
 }
 
+/* Section "MoE": the gating network is a linear layer before the softmax and TopK.  logits[t][e] =
+ * sum_h x[t][h] * w[e][h], with x [T][H] and w [E][H] in the activation type (0 = fp32, 1 = bf16 bits);
+ * every product is exact in double, the sum runs over h in ascending order in double and is rounded
+ * once to fp32. */
+int monta_oracle_gate(int64_t T, int H, int E, int dtype, const void *x, const void *w, float *logits)
+{
+    if (T < 0 || H < 1 || E < 1 || (dtype != 0 && dtype != 1)) return ORACLE_BAD_ARG;
+    for (int64_t t = 0; t < T; ++t)
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int h = 0; h < H; ++h) {
+                double a, b;
+                if (dtype == 0) {
+                    a = (double)((const float *)x)[t * H + h];
+                    b = (double)((const float *)w)[(int64_t)e * H + h];
+                } else {
+                    uint32_t ua = (uint32_t)((const uint16_t *)x)[t * H + h] << 16;
+                    uint32_t ub = (uint32_t)((const uint16_t *)w)[(int64_t)e * H + h] << 16;
+                    float fa, fb;
+                    memcpy(&fa, &ua, 4);
+                    memcpy(&fb, &ub, 4);
+                    a = fa;
+                    b = fb;
+                }
+                acc += a * b;
+            }
+            logits[t * E + e] = (float)acc;
+        }
+    return ORACLE_OK;
+}
+
 /* ------------------------------------------------------------------- plan */
 
 /* Capacity per expert.  The paper never drops tokens for capacity; the workloads

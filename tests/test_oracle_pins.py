@@ -134,6 +134,35 @@ def test_route_rejects_nonfinite():
         oracle.route(logits, 2)
 
 
+# --------------------------------------------------------------------- gate
+
+@pytest.mark.parametrize("dtype", [FP32, BF16])
+def test_gate_projection_is_a_matrix_product(dtype):
+    w = Workload("t", 50, 96, dtype, 7, 2, 1, 1, 1, 0.0)
+    _, x = workloads.make_inputs(w, seed=1)
+    wg = workloads.make_gate_weights(w, seed=1)
+    got = oracle.gate(x, wg)
+    xf = x if dtype == FP32 else workloads.bf16_bits_to_f32(x)
+    wf = wg if dtype == FP32 else workloads.bf16_bits_to_f32(wg)
+    ref = xf.astype(np.float64) @ wf.astype(np.float64).T            # library routine, its own summation order
+    assert got.shape == (50, 7) and got.dtype == np.float32
+    assert np.all(np.abs(got.astype(np.float64) - ref) <= 0.5000001 * ulp32(ref) + 1e-12)
+    # small integers: every partial sum is exact, so the result must be exact whatever the order
+    rng = np.random.default_rng(2)
+    xi = rng.integers(-8, 9, size=(20, 64)).astype(np.float32)
+    wi = rng.integers(-8, 9, size=(5, 64)).astype(np.float32)
+    if dtype == BF16:
+        xi_in, wi_in = workloads.f32_to_bf16_bits(xi), workloads.f32_to_bf16_bits(wi)
+    else:
+        xi_in, wi_in = xi, wi
+    np.testing.assert_array_equal(oracle.gate(xi_in, wi_in), (xi.astype(np.int64) @ wi.astype(np.int64).T).astype(np.float32))
+    # one-hot weights pick out columns: a transposed operand or a wrong stride would show
+    onehot = np.zeros((3, 64), np.float32)
+    onehot[0, 5] = onehot[1, 63] = onehot[2, 0] = 1.0
+    oh_in = workloads.f32_to_bf16_bits(onehot) if dtype == BF16 else onehot
+    np.testing.assert_array_equal(oracle.gate(xi_in, oh_in), xi[:, [5, 63, 0]])
+
+
 # --------------------------------------------------------------------- plan
 
 def test_capacity_formula():

@@ -124,3 +124,11 @@ def make_tied_logits(w: Workload, levels: int = 3, seed: int | None = None) -> n
     rng = np.random.default_rng(w.seed if seed is None else seed)
     vals = rng.integers(0, levels, size=(w.tokens, w.experts))
     return np.ascontiguousarray((vals.astype(np.float32) - 1.0) * np.float32(0.5))
+
+
+def make_gate_weights(w: Workload, seed: int | None = None) -> np.ndarray:
+    """Random-init gate weights [E, H] in the workload's activation type (uint16 bf16 bits or float32),
+    drawn as standard normals scaled by 1/sqrt(H) so that the logits are O(1)."""
+    rng = np.random.default_rng(10_000 + (w.seed if seed is None else seed))
+    wg = (rng.standard_normal((w.experts, w.hidden), dtype=np.float32) / np.float32(np.sqrt(w.hidden))).astype(np.float32)
+    return f32_to_bf16_bits(wg) if w.dtype == BF16 else np.ascontiguousarray(wg)
