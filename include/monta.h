@@ -122,6 +122,15 @@ int monta_ws_layout_query(const monta_cfg *cfg, monta_ws_layout *layout);
  * Needed once per workspace, before its first monta_route. */
 int monta_ws_init(const monta_cfg *cfg, void *ws, void *stream);
 
+/* Gate projection (section "MoE": the gating network is a linear layer whose output goes through softmax
+ * and TopK): logits[t][e] = sum_h x[t][h] * w_gate[e][h].  x [T][H] and w_gate [E][H] (one row per expert) in
+ * cfg->dtype, device pointers, 16-byte aligned; logits [T][E] fp32, device, written in full.  bf16 inputs are
+ * multiplied on the matrix cores with fp32 accumulation; the order of the additions is fixed for a given shape,
+ * so two calls on the same inputs agree bit for bit, and it differs from a left-to-right sum by at most
+ * H * 2^-24 * sum_h |x[t][h] * w_gate[e][h]|.  Uses only tokens, hidden, dtype and experts of cfg (all of it is
+ * validated); needs no workspace.  Nothing is owned or kept; the work is enqueued on `stream`. */
+int monta_gate(const monta_cfg *cfg, const void *x, const void *w_gate, float *logits, void *stream);
+
 /* Routing + Permutation plan.  logits [T][E] fp32 -> topk_idx [T][k] int32 (slot 0
  * = strongest choice; ties go to the lower expert index; selection is on the raw
  * logits), gates [T][k] fp32 (evaluated in fp64, rounded once), and every plan
@@ -252,7 +261,8 @@ enum monta_kernel_id {
     MONTA_K_UNREGATHER = 8,
     MONTA_K_UNREGATHER_COMBINE = 9, /* co-scheduled grid of the return pipeline */
     MONTA_K_ALLGATHER = 10,
-    MONTA_K_COUNT = 11
+    MONTA_K_GATE = 11,      /* gate projection                                */
+    MONTA_K_COUNT = 12
 };
 int monta_profile_enable(int on);
 int monta_profile_reset(void);

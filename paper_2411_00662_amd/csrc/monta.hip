@@ -479,6 +479,39 @@ int monta_ws_init(const monta_cfg *cfg, void *ws, void *stream)
     return MONTA_OK;
 }
 
+int monta_gate(const monta_cfg *cfg, const void *x, const void *w_gate, float *logits, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (!x || !w_gate || !logits) return MONTA_ERR_NULL;
+    if (misaligned(x, 16) || misaligned(w_gate, 16) || misaligned(logits, 4)) return MONTA_ERR_ALIGN;
+    const Shape &s = g.s;
+    const int64_t T = s.T;
+    const int H = cfg->hidden, E = s.E;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ProfScope ps(MONTA_K_GATE, st);
+    if (cfg->dtype == MONTA_BF16) {
+        // validate() guarantees H % 8 == 0 (rows are whole 16-byte vectors) and E <= 256 (at most 8 tiles)
+        const dim3 grid((unsigned)((T + kGateTokens - 1) / kGateTokens));
+        const u32x4 *xv = static_cast<const u32x4 *>(x), *wv = static_cast<const u32x4 *>(w_gate);
+        const int tiles = (E + 31) / 32;
+        if (tiles <= 1)
+            hipLaunchKernelGGL((gate_bf16_kernel<1, kGateThreads>), grid, dim3(kGateThreads), 0, st, xv, wv, logits, T, H, E);
+        else if (tiles <= 2)
+            hipLaunchKernelGGL((gate_bf16_kernel<2, kGateThreads>), grid, dim3(kGateThreads), 0, st, xv, wv, logits, T, H, E);
+        else if (tiles <= 4)
+            hipLaunchKernelGGL((gate_bf16_kernel<4, kGateThreads>), grid, dim3(kGateThreads), 0, st, xv, wv, logits, T, H, E);
+        else
+            hipLaunchKernelGGL((gate_bf16_kernel<8, 512>), grid, dim3(512), 0, st, xv, wv, logits, T, H, E);
+    } else {
+        hipLaunchKernelGGL(gate_f32_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, st,
+                           static_cast<const float4 *>(x), static_cast<const float4 *>(w_gate), logits, T, H, E);
+    }
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
 int monta_route(const monta_cfg *cfg, const float *logits, int32_t *topk_idx, float *gates, void *ws, void *stream)
 {
     Geometry g;

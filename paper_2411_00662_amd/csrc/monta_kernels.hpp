@@ -17,6 +17,9 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
+#ifndef MONTA_GATE_THREADS
+#define MONTA_GATE_THREADS 1024
+#endif
 #ifndef MONTA_MOVER_THREADS
 #define MONTA_MOVER_THREADS 256
 #endif
@@ -1021,6 +1024,129 @@ __global__ __launch_bounds__(kMoverThreads) void unregather_combine_kernel(const
             combine_rows_t<BF16, NV, decltype(l)::value, decltype(st)::value>(y_stage, gates, out, p.pos_stage, s, t0,
                                                                               nt, idx, n_comb_wg);
         });
+    }
+}
+
+// --------------------------------------------------------- gate projection
+//
+// logits[t][e] = sum_h x[t][h] * w[e][h]  (section "MoE": the gate is a linear layer ahead of softmax and TopK).
+// The contraction is read-bound on x: every element of x is used E times, far below what the matrix cores
+// need to be busy, so the kernel is laid out for the x stream and uses MFMA only to keep the arithmetic off
+// the critical path at large E.
+//
+// bf16: one workgroup owns 32 tokens; its waves split the hidden axis in blocks of 64 elements, taken round
+// robin.  In the 32x32x16 bf16 MFMA lane l supplies, for A, row l%32 and the 8 k-values 8*(l/32)..+7, and for
+// B column l%32 with the same k-values; the accumulator's element i of lane l is row (i/4)*8 + (l/32)*4 + i%4,
+// column l%32.  The sum over k has no order, so a lane reads 64 contiguous bytes of its row (four 16-byte
+// pieces, one per MFMA) and the same pieces of the weight row: x is fetched in whole 128-byte lines per row.
+// The waves' partial tiles are summed through LDS in a fixed order, so results are reproducible.
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kGateThreads = MONTA_GATE_THREADS;     // 16 waves: 64 KiB of x in flight per workgroup
+constexpr int kGateTokens = 32;                      // rows of one MFMA tile
+constexpr int kGateLdsFloats = 16384;                // 64 KiB of partial tiles
+
+// NT = tiles of 32 experts held in accumulators, THREADS = workgroup size (NT = 8 needs the 256 registers a
+// lane gets at 512 threads)
+template <int NT, int THREADS>
+__global__ __launch_bounds__(THREADS) void gate_bf16_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
+                                                                 float *__restrict__ logits, int64_t T, int H, int E)
+{
+    __shared__ float red[kGateLdsFloats];
+    constexpr int kGateWaves = THREADS / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 31, g = lane >> 5;
+    const int64_t t0 = (int64_t)blockIdx.x * kGateTokens;
+    const int64_t t = t0 + m;
+    const int cpr = H / 8;                  // 16-byte pieces per row
+    const int kblocks = (cpr + 7) / 8;      // blocks of 64 elements
+    const bool row_ok = t < T;
+    const u32x4 *xr = x + (row_ok ? t : 0) * cpr;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+
+    f32x16 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+
+    for (int kb = wave; kb < kblocks; kb += kGateWaves) {
+        const int c0 = kb * 8 + g * 4;
+        u32x4 a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = (row_ok && c0 + j < cpr) ? xr[c0 + j] : zero;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int n = nt * 32 + m;
+            const u32x4 *wr = w + (int64_t)(n < E ? n : 0) * cpr;
+            u32x4 b[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = (n < E && c0 + j < cpr) ? wr[c0 + j] : zero;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[j]),
+                                                                  __builtin_bit_cast(bf16x8, b[j]), acc[nt], 0, 0, 0);
+        }
+    }
+
+    // partial tiles -> LDS slots [slot][nt][row][col]; waves sharing a slot add in wave order, one round each
+    constexpr int kSlots = (kGateLdsFloats / 1024 / NT) < kGateWaves ? (kGateLdsFloats / 1024 / NT) : kGateWaves;
+    constexpr int kRounds = kGateWaves / kSlots;
+    static_assert(kSlots >= 1 && kSlots * kRounds == kGateWaves, "gate reduction: waves must fill the slots evenly");
+    const int slot = wave % kSlots, round = wave / kSlots;
+    for (int r = 0; r < kRounds; ++r) {
+        if (round == r) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int row = (i >> 2) * 8 + g * 4 + (i & 3);
+                    float *q = red + ((slot * NT + nt) * 32 + row) * 32 + m;
+                    *q = (r == 0) ? acc[nt][i] : *q + acc[nt][i];
+                }
+        }
+        __syncthreads();
+    }
+    const int64_t rows = (T - t0 < kGateTokens) ? (T - t0) : kGateTokens;
+    for (int64_t idx = threadIdx.x; idx < rows * E; idx += THREADS) {
+        const int row = (int)(idx / E), n = (int)(idx % E);
+        float sum = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < kSlots; ++sl) sum += red[((sl * NT + (n >> 5)) * 32 + row) * 32 + (n & 31)];
+        logits[t0 * E + idx] = sum;
+    }
+}
+
+// fp32 activations: one wave per token, eight experts at a time, fp32 fused multiply-adds and a shuffle reduction
+__global__ __launch_bounds__(256) void gate_f32_kernel(const float4 *__restrict__ x, const float4 *__restrict__ w,
+                                                       float *__restrict__ logits, int64_t T, int H, int E)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const int vpr = H / 4;
+    const float4 *xr = x + t * vpr;
+    for (int e0 = 0; e0 < E; e0 += 8) {
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        for (int v = lane; v < vpr; v += 64) {
+            const float4 xv = xr[v];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (e0 + j < E) {
+                    const float4 wv = w[(int64_t)(e0 + j) * vpr + v];
+                    acc[j] = fmaf(xv.x, wv.x, fmaf(xv.y, wv.y, fmaf(xv.z, wv.z, fmaf(xv.w, wv.w, acc[j]))));
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) acc[j] += __shfl_xor(acc[j], off, 64);
+            if (lane == 0 && e0 + j < E) logits[t * E + e0 + j] = acc[j];
+        }
     }
 }
 

@@ -115,6 +115,10 @@ def test_null_and_misaligned_pointers_fail_before_any_gpu_work():
     assert lib.monta_unregather_combine(c, fake, fake, fake, 3 * fake, fake, 0) == -1
     assert lib.monta_unregather_combine(c, fake, 2 * fake, fake, 3 * fake, 0, 0) == -3
     assert lib.monta_unregather_combine(c, fake, 2 * fake + 8, fake, 3 * fake, fake, 0) == -5
+    assert lib.monta_gate(c, fake, 0, fake, 0) == -3
+    assert lib.monta_gate(c, fake, fake, 0, 0) == -3
+    assert lib.monta_gate(c, fake + 8, fake, fake, 0) == -5
+    assert lib.monta_gate(c, fake, fake, fake + 2, 0) == -5
     assert lib.monta_ws_init(c, 0, 0) == -3
     assert lib.monta_copy(0, fake, 16, 0) == -3
     assert lib.monta_copy(fake, 2 * fake, 24, 0) == -1
@@ -125,6 +129,7 @@ def test_null_and_misaligned_pointers_fail_before_any_gpu_work():
     bad = good()
     bad.top_k = 0
     assert lib.monta_route(ctypes.byref(bad), fake, fake, fake, fake, 0) == -1
+    assert lib.monta_gate(ctypes.byref(bad), fake, fake, fake, 0) == -1
 
 
 def test_pipeline_mode_and_strerror():
