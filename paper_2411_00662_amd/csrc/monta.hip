@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <cstdlib>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -409,6 +410,53 @@ int check_act_ptrs(const void *a, const void *b)
     return MONTA_OK;
 }
 
+template <int MT, int NT, int KS, bool DEEP>
+int launch_gate(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, int H, int E, hipStream_t st)
+{
+    using G = GateTile<MT, NT, KS>;
+    static std::atomic<int> lds_opt_in{0};
+    if (!lds_opt_in.load()) {
+        // dynamic LDS above the default limit has to be asked for once per kernel
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gate_bf16_kernel<MT, NT, KS, DEEP>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::lds_bytes(32 * NT)));
+        lds_opt_in.store(1);
+    }
+    const unsigned grid = (unsigned)((T + G::kTokens - 1) / G::kTokens);
+    hipLaunchKernelGGL((gate_bf16_kernel<MT, NT, KS, DEEP>), dim3(grid), dim3(kGateThreads), G::lds_bytes(E), st, x, w, logits,
+                       T, H, E);
+    return MONTA_OK;
+}
+
+template <int NCH>
+int launch_gate_small(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, int H, int E, hipStream_t st)
+{
+    static std::atomic<int> lds_opt_in{0};
+    if (!lds_opt_in.load()) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gate_small_kernel<NCH>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)gate_small_lds_bytes(kGateSmallMaxChunk)));
+        lds_opt_in.store(1);
+    }
+    static std::atomic<int> cus{0};
+    if (!cus.load()) {
+        int dev = 0, n = 0;
+        HIP_TRY(hipGetDevice(&dev));
+        HIP_TRY(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        cus.store(n > 0 ? n : 256);
+    }
+    static const int wgs_per_cu = [] {
+        const char *e = getenv("MONTA_GATE_WGS_PER_CU");
+        const int v = e ? atoi(e) : 0;
+        return v >= 1 && v <= 4 ? v : 1;
+    }();
+    const int64_t ngroups = (T + kGateSmallTokens - 1) / kGateSmallTokens;
+    const int64_t resident = (int64_t)wgs_per_cu * cus.load();
+    const unsigned grid = (unsigned)(ngroups < resident ? ngroups : resident);
+    hipLaunchKernelGGL(gate_small_kernel<NCH>, dim3(grid), dim3(kGateThreads), gate_small_lds_bytes(H / NCH), st, x, w,
+                       logits, T, H, E, ngroups);
+    return MONTA_OK;
+}
+
 int launch_route(const Geometry &g, const PlanPtrs &p, const float *logits, int32_t *topk_idx, float *gates,
                  hipStream_t st)
 {
@@ -492,18 +540,25 @@ int monta_gate(const monta_cfg *cfg, const void *x, const void *w_gate, float *l
     hipStream_t st = static_cast<hipStream_t>(stream);
     ProfScope ps(MONTA_K_GATE, st);
     if (cfg->dtype == MONTA_BF16) {
-        // validate() guarantees H % 8 == 0 (rows are whole 16-byte vectors) and E <= 256 (at most 8 tiles)
-        const dim3 grid((unsigned)((T + kGateTokens - 1) / kGateTokens));
+        // validate() guarantees H % 8 == 0 (rows are whole 16-byte vectors) and E <= 256 (at most 8 tiles).
+        // Few token tiles: one workgroup per CU with a deep step; many: shallower steps, several workgroups per CU.
+        const int64_t tiles32 = (T + 31) / 32;
         const u32x4 *xv = static_cast<const u32x4 *>(x), *wv = static_cast<const u32x4 *>(w_gate);
-        const int tiles = (E + 31) / 32;
-        if (tiles <= 1)
-            hipLaunchKernelGGL((gate_bf16_kernel<1, kGateThreads>), grid, dim3(kGateThreads), 0, st, xv, wv, logits, T, H, E);
-        else if (tiles <= 2)
-            hipLaunchKernelGGL((gate_bf16_kernel<2, kGateThreads>), grid, dim3(kGateThreads), 0, st, xv, wv, logits, T, H, E);
-        else if (tiles <= 4)
-            hipLaunchKernelGGL((gate_bf16_kernel<4, kGateThreads>), grid, dim3(kGateThreads), 0, st, xv, wv, logits, T, H, E);
+        if (E <= kGateSmallExperts && H % 64 == 0 && H <= kGateSmallMaxChunk)
+            rc = launch_gate_small<1>(xv, wv, logits, T, H, E, st);
+        else if (E <= kGateSmallExperts && H % 128 == 0 && H <= 2 * kGateSmallMaxChunk)
+            rc = launch_gate_small<2>(xv, wv, logits, T, H, E, st);
+        else if (E <= 32)
+            rc = tiles32 >= 512 ? launch_gate<1, 1, 512, true>(xv, wv, logits, T, H, E, st)
+                                : launch_gate<1, 1, 1024, true>(xv, wv, logits, T, H, E, st);
+        else if (E <= 64)
+            rc = tiles32 >= 1024 ? launch_gate<2, 2, 256, true>(xv, wv, logits, T, H, E, st)
+                                 : launch_gate<1, 2, 512, true>(xv, wv, logits, T, H, E, st);
+        else if (E <= 128)
+            rc = launch_gate<1, 4, 256, true>(xv, wv, logits, T, H, E, st);
         else
-            hipLaunchKernelGGL((gate_bf16_kernel<8, 512>), grid, dim3(512), 0, st, xv, wv, logits, T, H, E);
+            rc = launch_gate<1, 8, 128, false>(xv, wv, logits, T, H, E, st);
+        if (rc) return rc;
     } else {
         hipLaunchKernelGGL(gate_f32_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, st,
                            static_cast<const float4 *>(x), static_cast<const float4 *>(w_gate), logits, T, H, E);

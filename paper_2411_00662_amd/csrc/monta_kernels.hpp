@@ -9,7 +9,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <type_traits>
 
 namespace monta {
 
@@ -17,9 +16,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
-#ifndef MONTA_GATE_THREADS
-#define MONTA_GATE_THREADS 1024
-#endif
 #ifndef MONTA_MOVER_THREADS
 #define MONTA_MOVER_THREADS 256
 #endif
@@ -1031,91 +1027,316 @@ __global__ __launch_bounds__(kMoverThreads) void unregather_combine_kernel(const
 //
 // logits[t][e] = sum_h x[t][h] * w[e][h]  (section "MoE": the gate is a linear layer ahead of softmax and TopK).
 // The contraction is read-bound on x: every element of x is used E times, far below what the matrix cores
-// need to be busy, so the kernel is laid out for the x stream and uses MFMA only to keep the arithmetic off
-// the critical path at large E.
+// need to be busy, so the kernel is laid out for the x stream and uses MFMA to keep the arithmetic off the
+// critical path at large E.
 //
-// bf16: one workgroup owns 32 tokens; its waves split the hidden axis in blocks of 64 elements, taken round
-// robin.  In the 32x32x16 bf16 MFMA lane l supplies, for A, row l%32 and the 8 k-values 8*(l/32)..+7, and for
-// B column l%32 with the same k-values; the accumulator's element i of lane l is row (i/4)*8 + (l/32)*4 + i%4,
-// column l%32.  The sum over k has no order, so a lane reads 64 contiguous bytes of its row (four 16-byte
-// pieces, one per MFMA) and the same pieces of the weight row: x is fetched in whole 128-byte lines per row.
-// The waves' partial tiles are summed through LDS in a fixed order, so results are reproducible.
+// bf16: a workgroup of 8 waves owns 32*MT tokens and all experts.  The hidden axis is cut into steps of KS
+// elements; a step's tile (the tokens' rows, then the experts' rows, KS*2 bytes each) is fetched with 16-byte
+// loads whose lanes run along a row, so every load instruction covers whole cache lines, parked in registers
+// while the previous tile is multiplied, and then laid into LDS with a 16-byte pad per row.  The 32x32x16 bf16
+// MFMA wants, from lane l, row l%32 and the 8 k-values 8*(l/32)..+7 of A and the same of B (column l%32); those
+// fragments are single 16-byte LDS reads.  The k-slices of a step are dealt round robin to the waves, each wave
+// carries MT*NT accumulator tiles (element i of lane l = row (i/4)*8 + (l/32)*4 + i%4, column l%32), and the
+// waves' partial tiles are added through LDS in a fixed order at the end, so results are reproducible.
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kGateThreads = MONTA_GATE_THREADS;     // 16 waves: 64 KiB of x in flight per workgroup
-constexpr int kGateTokens = 32;                      // rows of one MFMA tile
-constexpr int kGateLdsFloats = 16384;                // 64 KiB of partial tiles
+constexpr int kGateThreads = 512;
+constexpr int kGateWaves = kGateThreads / 64;
 
-// NT = tiles of 32 experts held in accumulators, THREADS = workgroup size (NT = 8 needs the 256 registers a
-// lane gets at 512 threads)
-template <int NT, int THREADS>
-__global__ __launch_bounds__(THREADS) void gate_bf16_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
+template <int MT, int NT, int KS>
+struct GateTile {
+    static constexpr int kTokens = 32 * MT;
+    static constexpr int kPiecesPerRow = KS / 8;                 // 16-byte pieces of one row of a step
+    static constexpr int kRowStride = KS * 2 + 16;               // bytes in LDS
+    static constexpr int kLoads = (32 * (MT + NT) * kPiecesPerRow + kGateThreads - 1) / kGateThreads;
+    static constexpr int kTiles = MT * NT;
+    // partial tiles of several waves side by side in 64 KiB; waves sharing a slot add one after the other
+    static constexpr int kSlots = (16 / kTiles) < kGateWaves ? (16 / kTiles) : kGateWaves;
+    static constexpr int kRounds = kGateWaves / kSlots;
+    static_assert(kSlots >= 1 && kSlots * kRounds == kGateWaves, "gate reduction: waves must fill the slots evenly");
+    static_assert((KS & (KS - 1)) == 0 && KS >= 128, "gate: KS must be a power of two, at least one k-slice per wave");
+    static constexpr size_t lds_bytes(int E)
+    {
+        const size_t tile = (size_t)(kTokens + E) * kRowStride, red = (size_t)kSlots * kTiles * 4096;
+        return tile > red ? tile : red;
+    }
+};
+
+// DEEP: two tiles in flight instead of one (not where the accumulators leave no registers for it)
+template <int MT, int NT, int KS, bool DEEP>
+__global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
                                                                  float *__restrict__ logits, int64_t T, int H, int E)
 {
-    __shared__ float red[kGateLdsFloats];
-    constexpr int kGateWaves = THREADS / 64;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    using G = GateTile<MT, NT, KS>;
+    extern __shared__ __align__(16) unsigned char gate_lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 31, g = lane >> 5;
-    const int64_t t0 = (int64_t)blockIdx.x * kGateTokens;
-    const int64_t t = t0 + m;
-    const int cpr = H / 8;                  // 16-byte pieces per row
-    const int kblocks = (cpr + 7) / 8;      // blocks of 64 elements
-    const bool row_ok = t < T;
-    const u32x4 *xr = x + (row_ok ? t : 0) * cpr;
+    const int64_t t0 = (int64_t)blockIdx.x * G::kTokens;
+    const int cpr = H / 8;                                        // 16-byte pieces per row in memory
+    const int pieces = (G::kTokens + E) * G::kPiecesPerRow;       // pieces of one tile
+    const int nsteps = (cpr + G::kPiecesPerRow - 1) / G::kPiecesPerRow;
     const u32x4 zero = {0u, 0u, 0u, 0u};
 
-    f32x16 acc[NT];
+    // Two tiles are kept in flight.  Every load is issued unconditionally, from a clamped in-bounds address, and
+    // what lies outside the matrices is replaced by zeros when the piece is laid into LDS: the number of loads
+    // between a tile's issue and its use is then fixed, and the wait before the use lets the younger tile's
+    // loads stay outstanding.
+    auto piece_ok = [&](int p, int step, int &row, int &c) {
+        row = p / G::kPiecesPerRow;
+        c = step * G::kPiecesPerRow + p % G::kPiecesPerRow;
+        return p < pieces && c < cpr && (row >= G::kTokens || t0 + row < T);
+    };
+    auto fetch = [&](u32x4(&pre)[G::kLoads], int step) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+        for (int q = 0; q < G::kLoads; ++q) {
+            int row, c;
+            const bool ok = piece_ok(tid + q * kGateThreads, step, row, c);
+            const u32x4 *src = x;
+            if (ok) src = (row < G::kTokens) ? x + (t0 + row) * cpr + c : w + (int64_t)(row - G::kTokens) * cpr + c;
+            pre[q] = *src;
+        }
+    };
+    auto stage = [&](const u32x4(&pre)[G::kLoads], int step) {
+        __syncthreads();                                          // the previous tile has been read by every wave
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+        for (int q = 0; q < G::kLoads; ++q) {
+            const int p = tid + q * kGateThreads;
+            int row, c;
+            const bool ok = piece_ok(p, step, row, c);
+            if (p < pieces)
+                *reinterpret_cast<u32x4 *>(gate_lds + (size_t)row * G::kRowStride + (p % G::kPiecesPerRow) * 16) =
+                    ok ? pre[q] : zero;
+        }
+        __syncthreads();
+    };
 
-    for (int kb = wave; kb < kblocks; kb += kGateWaves) {
-        const int c0 = kb * 8 + g * 4;
-        u32x4 a[4];
+    f32x16 acc[G::kTiles];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = (row_ok && c0 + j < cpr) ? xr[c0 + j] : zero;
+    for (int i = 0; i < G::kTiles; ++i)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int n = nt * 32 + m;
-            const u32x4 *wr = w + (int64_t)(n < E ? n : 0) * cpr;
-            u32x4 b[4];
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    auto multiply = [&]() {
+        for (int ks = wave; ks < KS / 16; ks += kGateWaves) {
+            const int off = ks * 32 + g * 16;
+            bf16x8 a[MT], b[NT];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = (n < E && c0 + j < cpr) ? wr[c0 + j] : zero;
+            for (int mt = 0; mt < MT; ++mt)
+                a[mt] = *reinterpret_cast<const bf16x8 *>(gate_lds + (size_t)(mt * 32 + m) * G::kRowStride + off);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[j]),
-                                                                  __builtin_bit_cast(bf16x8, b[j]), acc[nt], 0, 0, 0);
+            for (int nt = 0; nt < NT; ++nt) {
+                const int n = nt * 32 + m;
+                b[nt] = __builtin_bit_cast(bf16x8, zero);
+                if (n < E)
+                    b[nt] = *reinterpret_cast<const bf16x8 *>(gate_lds + (size_t)(G::kTokens + n) * G::kRowStride + off);
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[mt * NT + nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b[nt], acc[mt * NT + nt], 0, 0, 0);
+        }
+    };
+
+    if constexpr (DEEP) {
+        u32x4 pre0[G::kLoads], pre1[G::kLoads];
+        fetch(pre0, 0);
+        fetch(pre1, 1);                                           // past the last step: clamped loads, never used
+        for (int step = 0; step < nsteps; step += 2) {
+            stage(pre0, step);
+            fetch(pre0, step + 2);
+            multiply();
+            if (step + 1 < nsteps) {
+                stage(pre1, step + 1);
+                fetch(pre1, step + 3);
+                multiply();
+            }
+        }
+    } else {
+        u32x4 pre0[G::kLoads];
+        fetch(pre0, 0);
+        for (int step = 0; step < nsteps; ++step) {
+            stage(pre0, step);
+            fetch(pre0, step + 1);
+            multiply();
         }
     }
 
-    // partial tiles -> LDS slots [slot][nt][row][col]; waves sharing a slot add in wave order, one round each
-    constexpr int kSlots = (kGateLdsFloats / 1024 / NT) < kGateWaves ? (kGateLdsFloats / 1024 / NT) : kGateWaves;
-    constexpr int kRounds = kGateWaves / kSlots;
-    static_assert(kSlots >= 1 && kSlots * kRounds == kGateWaves, "gate reduction: waves must fill the slots evenly");
-    const int slot = wave % kSlots, round = wave / kSlots;
-    for (int r = 0; r < kRounds; ++r) {
+    // partial tiles -> LDS [slot][tile][row][col]
+    float *red = reinterpret_cast<float *>(gate_lds);
+    const int slot = wave % G::kSlots, round = wave / G::kSlots;
+    __syncthreads();                                              // the last tile is no longer needed
+    for (int r = 0; r < G::kRounds; ++r) {
         if (round == r) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
+            for (int i = 0; i < G::kTiles; ++i)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int row = (i >> 2) * 8 + g * 4 + (i & 3);
-                    float *q = red + ((slot * NT + nt) * 32 + row) * 32 + m;
-                    *q = (r == 0) ? acc[nt][i] : *q + acc[nt][i];
+                for (int j = 0; j < 16; ++j) {
+                    const int row = (j >> 2) * 8 + g * 4 + (j & 3);
+                    float *q = red + ((slot * G::kTiles + i) * 32 + row) * 32 + m;
+                    *q = (r == 0) ? acc[i][j] : *q + acc[i][j];
                 }
         }
         __syncthreads();
     }
-    const int64_t rows = (T - t0 < kGateTokens) ? (T - t0) : kGateTokens;
-    for (int64_t idx = threadIdx.x; idx < rows * E; idx += THREADS) {
+    const int64_t rows = (T - t0 < G::kTokens) ? (T - t0) : G::kTokens;
+    for (int64_t idx = tid; idx < rows * E; idx += kGateThreads) {
         const int row = (int)(idx / E), n = (int)(idx % E);
+        const int tile = (row >> 5) * NT + (n >> 5);
         float sum = 0.f;
 #pragma unroll
-        for (int sl = 0; sl < kSlots; ++sl) sum += red[((sl * NT + (n >> 5)) * 32 + row) * 32 + (n & 31)];
+        for (int sl = 0; sl < G::kSlots; ++sl) sum += red[((sl * G::kTiles + tile) * 32 + (row & 31)) * 32 + (n & 31)];
         logits[t0 * E + idx] = sum;
+    }
+}
+
+// bf16, at most 8 experts, H <= 8192 and a multiple of 64*NCH: the shapes of the paper's layers.  A tile of 32
+// consecutive rows walked in column steps touches memory in short strided runs, which the memory system serves
+// well below its streaming rate; here a workgroup reads 8 whole consecutive rows at a time (NCH = 1; halves of
+// them if NCH = 2), i.e. one contiguous run of up to 64 KiB.  The 32 MFMA rows are (quarter of the row chunk,
+// token) pairs and the 32 columns (quarter, expert) pairs: row qk*8+tok holds x[tok][quarter qk], column qk'*8+e
+// holds w[e][quarter qk'], so the diagonal blocks qk = qk' of the accumulator carry the four quarter sums of
+// every (token, expert) logit, and the off-diagonal blocks, which would be idle columns anyway with so few
+// experts, are ignored.  The weights never change, so a persistent workgroup keeps its B fragments in registers
+// for the whole launch: wave v owns steps v, v+8, ... of each quarter.  Sums over quarters (two lane shuffles),
+// over waves (LDS, fixed order) and over chunks (the accumulator) are in a fixed order: results are reproducible.
+
+constexpr int kGateSmallTokens = 8;          // rows of one tile
+constexpr int kGateSmallExperts = 8;         // expert slots of one quarter
+constexpr int kGateSmallMaxChunk = 4096;     // elements of a row in LDS at a time
+constexpr int kGateSmallSteps = kGateSmallMaxChunk / 64 / kGateWaves;   // MFMA steps of a chunk per wave, at most
+constexpr int kGateSmallLoads = kGateSmallTokens * kGateSmallMaxChunk / 8 / kGateThreads;
+
+__host__ __device__ constexpr int gate_small_quarter_stride(int chunk) { return chunk / 2 + 128; }      // bytes
+__host__ __device__ constexpr int gate_small_row_stride(int chunk) { return 4 * gate_small_quarter_stride(chunk) + 16; }
+__host__ __device__ constexpr size_t gate_small_lds_bytes(int chunk)
+{
+    return (size_t)kGateSmallTokens * gate_small_row_stride(chunk) +
+           sizeof(float) * kGateWaves * kGateSmallTokens * kGateSmallExperts;
+}
+
+template <int NCH>
+__global__ __launch_bounds__(kGateThreads) void gate_small_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
+                                                                  float *__restrict__ logits, int64_t T, int H, int E,
+                                                                  int64_t ngroups)
+{
+    extern __shared__ __align__(16) unsigned char gate_lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+    const int chunk = H / NCH;                       // elements, a multiple of 64
+    const int ppr = chunk / 8, ppq = chunk / 32;     // 16-byte pieces per row chunk / per quarter
+    const int cpr = H / 8;
+    const int QS = gate_small_quarter_stride(chunk), RS = gate_small_row_stride(chunk);
+    const int nsteps = chunk / 64;                   // MFMA steps per chunk: a quarter is nsteps*16 elements
+    float *red = reinterpret_cast<float *>(gate_lds + (size_t)kGateSmallTokens * RS);
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+
+    // This thread's pieces of a tile, fixed for the whole launch: piece p = tid + q*threads is row p / ppr, column
+    // p % ppr.  One division per thread; the others follow by stepping (integer division is slow here).
+    int piece_row[kGateSmallLoads], piece_col[kGateSmallLoads], piece_lds[kGateSmallLoads];
+    {
+        const int step_rows = kGateThreads / ppr, step_cols = kGateThreads % ppr;
+        int row = tid / ppr, col = tid % ppr;
+#pragma unroll
+        for (int q = 0; q < kGateSmallLoads; ++q) {
+            const bool in_tile = row < kGateSmallTokens;
+            const int qk = (col >= ppq ? 1 : 0) + (col >= 2 * ppq ? 1 : 0) + (col >= 3 * ppq ? 1 : 0);
+            piece_row[q] = in_tile ? row : -1;
+            piece_col[q] = in_tile ? col : 0;
+            piece_lds[q] = in_tile ? row * RS + qk * QS + (col - qk * ppq) * 16 : 0;
+            row += step_rows;
+            col += step_cols;
+            if (col >= ppr) {
+                col -= ppr;
+                ++row;
+            }
+        }
+    }
+    // fragment address of this lane at step 0: row lane%8, quarter (lane%32)/8, k-values 8*(lane/32)..+7
+    const unsigned char *frag = gate_lds + (size_t)(lane & 7) * RS + (size_t)((lane & 31) >> 3) * QS + g * 16;
+
+    // Loads are issued unconditionally, from clamped addresses, all of a tile before the first use; what lies
+    // outside the matrix becomes zeros when the tile is laid into LDS.
+    u32x4 pre[kGateSmallLoads];
+    auto fetch = [&](const u32x4 *base, int64_t first_row, int64_t row_limit, int c) {
+        unsigned ok = 0;
+#pragma unroll
+        for (int q = 0; q < kGateSmallLoads; ++q) {
+            const int64_t r = first_row + piece_row[q];
+            const bool live = piece_row[q] >= 0 && r < row_limit;
+            pre[q] = *(live ? base + r * cpr + c * ppr + piece_col[q] : base);
+            ok |= (live ? 1u : 0u) << q;
+        }
+        return ok;
+    };
+    auto lay = [&](unsigned ok) {
+        __syncthreads();                                          // the previous tile has been read by every wave
+#pragma unroll
+        for (int q = 0; q < kGateSmallLoads; ++q)
+            if (piece_row[q] >= 0)
+                *reinterpret_cast<u32x4 *>(gate_lds + piece_lds[q]) = ((ok >> q) & 1u) ? pre[q] : zero;
+        __syncthreads();
+    };
+
+    // weights -> LDS (same layout, expert rows) -> B fragments in registers
+    bf16x8 bfrag[NCH][kGateSmallSteps];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        lay(fetch(w, 0, E, c));
+#pragma unroll
+        for (int i = 0; i < kGateSmallSteps; ++i) {
+            const int st = wave + i * kGateWaves;
+            bfrag[c][i] = __builtin_bit_cast(bf16x8, zero);
+            if (st < nsteps) bfrag[c][i] = *reinterpret_cast<const bf16x8 *>(frag + st * 32);
+        }
+    }
+
+    f32x16 acc;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+
+    int64_t grp = blockIdx.x;
+    unsigned ok = fetch(x, grp * kGateSmallTokens, T, 0);
+    for (; grp < ngroups; grp += gridDim.x) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            lay(ok);
+            // the next tile is in flight during the MFMAs
+            ok = (c + 1 < NCH) ? fetch(x, grp * kGateSmallTokens, T, c + 1)
+                               : fetch(x, (grp + gridDim.x) * kGateSmallTokens, T, 0);
+#pragma unroll
+            for (int i = 0; i < kGateSmallSteps; ++i) {
+                const int st = wave + i * kGateWaves;
+                if (st < nsteps)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(frag + st * 32),
+                                                                  bfrag[c][i], acc, 0, 0, 0);
+            }
+        }
+        // accumulator element j of this lane: row (j/4)*8 + g*4 + j%4 = (quarter j/4, token g*4 + j%4), column
+        // (quarter (lane%32)/8, expert lane%8): keep the diagonal block, add the quarters, then the waves
+        const int qn = (lane & 31) >> 3;
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[i] = qn == 0 ? acc[i] : qn == 1 ? acc[4 + i] : qn == 2 ? acc[8 + i] : acc[12 + i];
+            v[i] += __shfl_xor(v[i], 8, 64);
+            v[i] += __shfl_xor(v[i], 16, 64);
+        }
+        if (qn == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[(wave * kGateSmallTokens + g * 4 + i) * kGateSmallExperts + (lane & 7)] = v[i];
+        }
+        __syncthreads();
+        if (tid < kGateSmallTokens * kGateSmallExperts) {
+            const int tok = tid >> 3, e = tid & 7;
+            float sum = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < kGateWaves; ++wv) sum += red[(wv * kGateSmallTokens + tok) * kGateSmallExperts + e];
+            const int64_t t = grp * kGateSmallTokens + tok;
+            if (e < E && t < T) logits[t * E + e] = sum;
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = 0.f;
     }
 }
 

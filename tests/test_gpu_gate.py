@@ -62,7 +62,10 @@ def to_act(a, dtype):
 # (T, H, E): several 32-token tiles with a ragged last one, hidden sizes that are not whole 64-element blocks,
 # expert counts on both sides of the 32-wide tiles up to the library's limit
 SHAPES = [(1, 8, 1), (31, 64, 7), (100, 200, 8), (257, 1032, 33), (64, 4096, 64), (96, 72, 100), (40, 520, 256),
-          (1000, 4096, 8), (33, 8, 129)]
+          (1000, 4096, 8), (33, 8, 129),
+          # at most 8 experts and whole 64-element quarters: the persistent whole-row kernel, one and two chunks per row,
+          # quarters that are not powers of two, fewer MFMA steps than waves, more groups than workgroups
+          (70, 8192, 8), (45, 7168, 3), (19, 1088, 5), (300, 2048, 2), (64, 128, 8), (9, 4160, 1), (5000, 256, 6)]
 
 
 @pytest.mark.parametrize("dtype", [BF16, FP32])
