@@ -427,14 +427,15 @@ int launch_gate(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, int H,
     return MONTA_OK;
 }
 
-template <int NCH>
-int launch_gate_small(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, int H, int E, hipStream_t st)
+template <int NCH, int THREADS, int MAXCHUNK>
+int launch_gate_small(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, int H, int E, int wgs_per_cu,
+                      hipStream_t st)
 {
     static std::atomic<int> lds_opt_in{0};
     if (!lds_opt_in.load()) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gate_small_kernel<NCH>),
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gate_small_kernel<NCH, THREADS, MAXCHUNK>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)gate_small_lds_bytes(kGateSmallMaxChunk)));
+                                    (int)gate_small_lds_bytes(MAXCHUNK, THREADS)));
         lds_opt_in.store(1);
     }
     static std::atomic<int> cus{0};
@@ -444,17 +445,25 @@ int launch_gate_small(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, 
         HIP_TRY(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
         cus.store(n > 0 ? n : 256);
     }
-    static const int wgs_per_cu = [] {
-        const char *e = getenv("MONTA_GATE_WGS_PER_CU");
-        const int v = e ? atoi(e) : 0;
-        return v >= 1 && v <= 4 ? v : 1;
-    }();
     const int64_t ngroups = (T + kGateSmallTokens - 1) / kGateSmallTokens;
     const int64_t resident = (int64_t)wgs_per_cu * cus.load();
     const unsigned grid = (unsigned)(ngroups < resident ? ngroups : resident);
-    hipLaunchKernelGGL(gate_small_kernel<NCH>, dim3(grid), dim3(kGateThreads), gate_small_lds_bytes(H / NCH), st, x, w,
-                       logits, T, H, E, ngroups);
+    hipLaunchKernelGGL((gate_small_kernel<NCH, THREADS, MAXCHUNK>), dim3(grid), dim3(THREADS),
+                       gate_small_lds_bytes(H / NCH, THREADS), st, x, w, logits, T, H, E, ngroups);
     return MONTA_OK;
+}
+
+// The whole-row kernel for at most 8 experts; returns 1 if the shape does not fit it.  Measured on MI355X: tiles
+// of 8 rows x 4 KiB serve rows of up to 8 KiB best (a workgroup then sees more, smaller tiles and starts
+// sooner), tiles of 8 rows x 8 KiB longer rows; more than one workgroup per CU only repeats the weight set-up.
+int launch_gate_small_any(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, int H, int E, hipStream_t st)
+{
+    if (E > kGateSmallExperts) return 1;
+    if (H <= 2048 && H % 64 == 0) return launch_gate_small<1, 512, 2048>(x, w, logits, T, H, E, 1, st);
+    if (H <= 4096 && H % 128 == 0) return launch_gate_small<2, 512, 2048>(x, w, logits, T, H, E, 1, st);
+    if (H <= 4096 && H % 64 == 0) return launch_gate_small<1, 512, 4096>(x, w, logits, T, H, E, 1, st);
+    if (H <= 8192 && H % 128 == 0) return launch_gate_small<2, 512, 4096>(x, w, logits, T, H, E, 1, st);
+    return 1;
 }
 
 int launch_route(const Geometry &g, const PlanPtrs &p, const float *logits, int32_t *topk_idx, float *gates,
@@ -544,10 +553,10 @@ int monta_gate(const monta_cfg *cfg, const void *x, const void *w_gate, float *l
         // Few token tiles: one workgroup per CU with a deep step; many: shallower steps, several workgroups per CU.
         const int64_t tiles32 = (T + 31) / 32;
         const u32x4 *xv = static_cast<const u32x4 *>(x), *wv = static_cast<const u32x4 *>(w_gate);
-        if (E <= kGateSmallExperts && H % 64 == 0 && H <= kGateSmallMaxChunk)
-            rc = launch_gate_small<1>(xv, wv, logits, T, H, E, st);
-        else if (E <= kGateSmallExperts && H % 128 == 0 && H <= 2 * kGateSmallMaxChunk)
-            rc = launch_gate_small<2>(xv, wv, logits, T, H, E, st);
+        rc = launch_gate_small_any(xv, wv, logits, T, H, E, st);
+        if (rc <= 0) {
+            if (rc) return rc;
+        }
         else if (E <= 32)
             rc = tiles32 >= 512 ? launch_gate<1, 1, 512, true>(xv, wv, logits, T, H, E, st)
                                 : launch_gate<1, 1, 1024, true>(xv, wv, logits, T, H, E, st);

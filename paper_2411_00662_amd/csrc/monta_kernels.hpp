@@ -1204,23 +1204,27 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const u32x4 *__
 
 constexpr int kGateSmallTokens = 8;          // rows of one tile
 constexpr int kGateSmallExperts = 8;         // expert slots of one quarter
-constexpr int kGateSmallMaxChunk = 4096;     // elements of a row in LDS at a time
-constexpr int kGateSmallSteps = kGateSmallMaxChunk / 64 / kGateWaves;   // MFMA steps of a chunk per wave, at most
-constexpr int kGateSmallLoads = kGateSmallTokens * kGateSmallMaxChunk / 8 / kGateThreads;
 
 __host__ __device__ constexpr int gate_small_quarter_stride(int chunk) { return chunk / 2 + 128; }      // bytes
 __host__ __device__ constexpr int gate_small_row_stride(int chunk) { return 4 * gate_small_quarter_stride(chunk) + 16; }
-__host__ __device__ constexpr size_t gate_small_lds_bytes(int chunk)
+__host__ __device__ constexpr size_t gate_small_lds_bytes(int chunk, int threads)
 {
+    // the tile, then two buffers of partial sums [wave][quarter][token][expert]
     return (size_t)kGateSmallTokens * gate_small_row_stride(chunk) +
-           sizeof(float) * kGateWaves * kGateSmallTokens * kGateSmallExperts;
+           2 * sizeof(float) * (threads / 64) * 4 * kGateSmallTokens * kGateSmallExperts;
 }
 
-template <int NCH>
-__global__ __launch_bounds__(kGateThreads) void gate_small_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
-                                                                  float *__restrict__ logits, int64_t T, int H, int E,
-                                                                  int64_t ngroups)
+// NCH chunks per row, THREADS per workgroup, MAXCHUNK = most elements of a row in LDS at a time
+template <int NCH, int THREADS, int MAXCHUNK>
+__global__ __launch_bounds__(THREADS) void gate_small_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
+                                                             float *__restrict__ logits, int64_t T, int H, int E,
+                                                             int64_t ngroups)
 {
+    constexpr int kGateThreads = THREADS, kGateWaves = THREADS / 64;
+    constexpr int kGateSmallSteps = MAXCHUNK / 64 / kGateWaves;     // MFMA steps of a chunk per wave, at most
+    constexpr int kGateSmallLoads = kGateSmallTokens * MAXCHUNK / 8 / THREADS;
+    constexpr int kRedFloats = kGateWaves * 4 * kGateSmallTokens * kGateSmallExperts;
+    static_assert(kGateSmallSteps >= 1 && kGateSmallLoads >= 1, "gate_small_kernel: chunk too small for the workgroup");
     extern __shared__ __align__(16) unsigned char gate_lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
     const int chunk = H / NCH;                       // elements, a multiple of 64
@@ -1257,37 +1261,45 @@ __global__ __launch_bounds__(kGateThreads) void gate_small_kernel(const u32x4 *_
 
     // Loads are issued unconditionally, from clamped addresses, all of a tile before the first use; what lies
     // outside the matrix becomes zeros when the tile is laid into LDS.
-    u32x4 pre[kGateSmallLoads];
-    auto fetch = [&](const u32x4 *base, int64_t first_row, int64_t row_limit, int c) {
+    auto fetch = [&](u32x4(&dst)[kGateSmallLoads], const u32x4 *base, int64_t first_row, int64_t row_limit, int c) {
         unsigned ok = 0;
 #pragma unroll
         for (int q = 0; q < kGateSmallLoads; ++q) {
             const int64_t r = first_row + piece_row[q];
             const bool live = piece_row[q] >= 0 && r < row_limit;
-            pre[q] = *(live ? base + r * cpr + c * ppr + piece_col[q] : base);
+            dst[q] = *(live ? base + r * cpr + c * ppr + piece_col[q] : base);
             ok |= (live ? 1u : 0u) << q;
         }
         return ok;
     };
-    auto lay = [&](unsigned ok) {
+    auto lay = [&](const u32x4(&src)[kGateSmallLoads], unsigned ok) {
         __syncthreads();                                          // the previous tile has been read by every wave
 #pragma unroll
         for (int q = 0; q < kGateSmallLoads; ++q)
             if (piece_row[q] >= 0)
-                *reinterpret_cast<u32x4 *>(gate_lds + piece_lds[q]) = ((ok >> q) & 1u) ? pre[q] : zero;
+                *reinterpret_cast<u32x4 *>(gate_lds + piece_lds[q]) = ((ok >> q) & 1u) ? src[q] : zero;
         __syncthreads();
     };
 
-    // weights -> LDS (same layout, expert rows) -> B fragments in registers
+    // weights -> LDS (same layout, expert rows) -> B fragments in registers, while the first tile of x is already
+    // on its way
+    u32x4 pre[kGateSmallLoads];
+    int64_t grp = blockIdx.x;
+    unsigned ok = 0;
     bf16x8 bfrag[NCH][kGateSmallSteps];
+    {
+        u32x4 wpre[kGateSmallLoads];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        lay(fetch(w, 0, E, c));
+        for (int c = 0; c < NCH; ++c) {
+            const unsigned wok = fetch(wpre, w, 0, E, c);
+            if (c == NCH - 1) ok = fetch(pre, x, grp * kGateSmallTokens, T, 0);
+            lay(wpre, wok);
 #pragma unroll
-        for (int i = 0; i < kGateSmallSteps; ++i) {
-            const int st = wave + i * kGateWaves;
-            bfrag[c][i] = __builtin_bit_cast(bf16x8, zero);
-            if (st < nsteps) bfrag[c][i] = *reinterpret_cast<const bf16x8 *>(frag + st * 32);
+            for (int i = 0; i < kGateSmallSteps; ++i) {
+                const int st = wave + i * kGateWaves;
+                bfrag[c][i] = __builtin_bit_cast(bf16x8, zero);
+                if (st < nsteps) bfrag[c][i] = *reinterpret_cast<const bf16x8 *>(frag + st * 32);
+            }
         }
     }
 
@@ -1295,48 +1307,60 @@ __global__ __launch_bounds__(kGateThreads) void gate_small_kernel(const u32x4 *_
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[j] = 0.f;
 
-    int64_t grp = blockIdx.x;
-    unsigned ok = fetch(x, grp * kGateSmallTokens, T, 0);
+    // The waves' partial sums of a group go to LDS, and 64 threads add them up and store the logits one tile
+    // later, behind that tile's barriers: no barrier of its own, and the additions run beside the other waves'
+    // MFMAs.  Two buffers, used alternately.
+    const int qn = (lane & 31) >> 3;
+    int64_t pending = -1;                           // group whose partial sums wait in red[parity]
+    int parity = 0;
+    auto finish = [&](int64_t done, int buf) {
+        if (tid < kGateSmallTokens * kGateSmallExperts) {
+            const float *src = red + buf * kRedFloats + tid;      // [wave][quarter][token][expert], tid = token*8 + expert
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < kGateWaves * 4; ++i) sum += src[i * kGateSmallTokens * kGateSmallExperts];
+            const int64_t t = done * kGateSmallTokens + (tid >> 3);
+            if ((tid & 7) < E && t < T) logits[t * E + (tid & 7)] = sum;
+        }
+    };
+
     for (; grp < ngroups; grp += gridDim.x) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            lay(ok);
+            lay(pre, ok);
             // the next tile is in flight during the MFMAs
-            ok = (c + 1 < NCH) ? fetch(x, grp * kGateSmallTokens, T, c + 1)
-                               : fetch(x, (grp + gridDim.x) * kGateSmallTokens, T, 0);
+            ok = (c + 1 < NCH) ? fetch(pre, x, grp * kGateSmallTokens, T, c + 1)
+                               : fetch(pre, x, (grp + gridDim.x) * kGateSmallTokens, T, 0);
+            if (pending >= 0) {
+                finish(pending, parity ^ 1);
+                pending = -1;
+            }
+            // steps past the chunk's end multiply zeros (their B fragments are zero, A is made zero here)
+            bf16x8 a[kGateSmallSteps];
 #pragma unroll
             for (int i = 0; i < kGateSmallSteps; ++i) {
                 const int st = wave + i * kGateWaves;
-                if (st < nsteps)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(frag + st * 32),
-                                                                  bfrag[c][i], acc, 0, 0, 0);
+                a[i] = __builtin_bit_cast(bf16x8, zero);
+                if (st < nsteps) a[i] = *reinterpret_cast<const bf16x8 *>(frag + st * 32);
             }
+#pragma unroll
+            for (int i = 0; i < kGateSmallSteps; ++i)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bfrag[c][i], acc, 0, 0, 0);
         }
         // accumulator element j of this lane: row (j/4)*8 + g*4 + j%4 = (quarter j/4, token g*4 + j%4), column
-        // (quarter (lane%32)/8, expert lane%8): keep the diagonal block, add the quarters, then the waves
-        const int qn = (lane & 31) >> 3;
-        float v[4];
+        // (quarter (lane%32)/8, expert lane%8): only the diagonal blocks, quarter j/4 = quarter of the column, count
+        float *dst = red + parity * kRedFloats + ((wave * 4 + qn) * kGateSmallTokens + g * 4) * kGateSmallExperts + (lane & 7);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[i] = qn == 0 ? acc[i] : qn == 1 ? acc[4 + i] : qn == 2 ? acc[8 + i] : acc[12 + i];
-            v[i] += __shfl_xor(v[i], 8, 64);
-            v[i] += __shfl_xor(v[i], 16, 64);
-        }
-        if (qn == 0) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) red[(wave * kGateSmallTokens + g * 4 + i) * kGateSmallExperts + (lane & 7)] = v[i];
-        }
-        __syncthreads();
-        if (tid < kGateSmallTokens * kGateSmallExperts) {
-            const int tok = tid >> 3, e = tid & 7;
-            float sum = 0.f;
-#pragma unroll
-            for (int wv = 0; wv < kGateWaves; ++wv) sum += red[(wv * kGateSmallTokens + tok) * kGateSmallExperts + e];
-            const int64_t t = grp * kGateSmallTokens + tok;
-            if (e < E && t < T) logits[t * E + e] = sum;
-        }
+        for (int i = 0; i < 4; ++i)
+            dst[i * kGateSmallExperts] = qn == 0 ? acc[i] : qn == 1 ? acc[4 + i] : qn == 2 ? acc[8 + i] : acc[12 + i];
+        pending = grp;
+        parity ^= 1;
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+    }
+    if (pending >= 0) {
+        __syncthreads();
+        finish(pending, parity ^ 1);
     }
 }
 
