@@ -68,6 +68,9 @@ def main():
                     help="direct: combine reads the expert output in FINAL layout (the headline path); mirror: the "
                          "second AllToAll mirrored (unregather + staged combine pipeline), 2R more rows moved")
     ap.add_argument("--padded", type=int, default=0, help="1: capacity-padded [E][C][H] layout of FINAL (zero-filled padding)")
+    ap.add_argument("--gate", type=int, default=0,
+                    help="1: the step starts one stage earlier, at the gate projection (monta_gate: logits = x * w_gate^T "
+                         "with random-init weights); 0: at the logits, as the headline metric is defined")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     args = ap.parse_args()
@@ -103,8 +106,12 @@ def main():
 
     mirror = args.return_path == "mirror"
     y_stage = torch.empty_like(b.stage) if mirror else None
+    w_gate_host = workloads.make_gate_weights(w) if args.gate else None
+    w_gate = m.buffers.to_device_act(cfg, w_gate_host) if args.gate else None
 
     def step():
+        if args.gate:
+            m.monta_gate(cfg, b.x, w_gate, b.logits, stream)
         m.monta_route_dispatch_regather(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, b.ws, stream)
         if mirror:
             m.monta_unregather_combine(cfg, b.final, y_stage, b.gates, b.out, b.ws, stream)
@@ -157,6 +164,9 @@ def main():
         ab["total"] += 2 * ab["R"] * ab["row"]
         ab["unregather_s"] = ab["regather_s"]
         ab["combine_s"] = [ab["regather_s"][j] // 2 + (w.tokens // w.slices) * ab["row"] for j in range(w.slices)]
+    if args.gate:
+        ab["gate"] = (w.tokens + w.experts) * ab["row"] + w.tokens * w.experts * 4
+        ab["total"] += ab["gate"]
     eff_gbps = ab["total"] / (ms_per_step * 1e-3) / 1e9
 
     # ---- per-kernel durations: HIP events around every launch, on the launching stream, eager launches
@@ -185,7 +195,7 @@ def main():
         m.monta_profile_reset()
         S = w.slices
         per_launch = {"pack": None, "regather": None, "pack_regather": None, "combine": ab["combine"],
-                      "plan_pack": ab["pack_s"][0] + ab["plan"]}
+                      "plan_pack": ab["pack_s"][0] + ab["plan"], "gate": ab.get("gate")}
         if "pack" in kernels:
             npk = round(kernels["pack"]["launches_per_step"])
             per_launch["pack"] = (sum(ab["pack_s"]) if mode != 1 else ab["pack_s"][0]) / npk
@@ -203,7 +213,7 @@ def main():
                 per_launch["unregather_combine"] = sum(ab["unregather_s"][j] + ab["combine_s"][j - 1]
                                                        for j in range(1, S_)) / (S_ - 1)
         movers = [kname for kname in ("pack", "regather", "pack_regather", "combine", "plan_pack", "unregather",
-                                      "unregather_combine") if kname in kernels]
+                                      "unregather_combine", "gate") if kname in kernels]
         dom = max(movers, key=lambda kname: kernels[kname]["us_per_step"])
         achieved = per_launch[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e9
         # HBM-side bytes per launch of that kernel from rocprofv3 counters (profiles/traffic.json, written by
@@ -245,6 +255,8 @@ def main():
         budget = 12.0
         while reps < 20 and spent < budget:
             c0 = time.perf_counter()
+            if args.gate:
+                logits = oracle.gate(x, w_gate_host)
             oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm,
                            padded=w.padded)
             spent += time.perf_counter() - c0
@@ -262,6 +274,7 @@ def main():
                    "top_k": w.top_k, "ep": w.ep, "tp": w.tp, "slices": w.slices,
                    "capacity_factor": w.capacity_factor, "kept_rows": ab["R"], "alive_tokens": ab["alive"],
                    "pipeline_mode": mode, "hip_graph": use_graph, "return_path": args.return_path, "padded": w.padded,
+                   "gate": bool(args.gate),
                    "parallelism": "1 GPU, virtual ep/tp"},
         "effective_GBps": round(eff_gbps, 1), "pct_of_hbm_peak": round(100 * eff_gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_bytes_per_step": int(ab["total"]),
