@@ -410,19 +410,19 @@ int check_act_ptrs(const void *a, const void *b)
     return MONTA_OK;
 }
 
-template <int MT, int NT, int KS, bool DEEP>
+template <int MT, int NT, int KS, bool DEEP, bool SPLIT = false>
 int launch_gate(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, int H, int E, hipStream_t st)
 {
     using G = GateTile<MT, NT, KS>;
     static std::atomic<int> lds_opt_in{0};
     if (!lds_opt_in.load()) {
         // dynamic LDS above the default limit has to be asked for once per kernel
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gate_bf16_kernel<MT, NT, KS, DEEP>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::lds_bytes(32 * NT)));
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gate_bf16_kernel<MT, NT, KS, DEEP, SPLIT>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::lds_bytes(32 * NT, !SPLIT)));
         lds_opt_in.store(1);
     }
     const unsigned grid = (unsigned)((T + G::kTokens - 1) / G::kTokens);
-    hipLaunchKernelGGL((gate_bf16_kernel<MT, NT, KS, DEEP>), dim3(grid), dim3(kGateThreads), G::lds_bytes(E), st, x, w, logits,
+    hipLaunchKernelGGL((gate_bf16_kernel<MT, NT, KS, DEEP, SPLIT>), dim3(grid), dim3(kGateThreads), G::lds_bytes(E, !SPLIT), st, x, w, logits,
                        T, H, E);
     return MONTA_OK;
 }
@@ -560,13 +560,18 @@ int monta_gate(const monta_cfg *cfg, const void *x, const void *w_gate, float *l
         else if (E <= 32)
             rc = tiles32 >= 512 ? launch_gate<1, 1, 512, true>(xv, wv, logits, T, H, E, st)
                                 : launch_gate<1, 1, 1024, true>(xv, wv, logits, T, H, E, st);
+        // More experts: with at least one 128-token workgroup per CU, every wave owns whole output tiles (W_g is
+        // re-read once per 128 tokens instead of once per 32-64, and the small tiles let 3 workgroups share a CU);
+        // with fewer tokens, 32-token workgroups with the k-slices dealt to the waves keep the chip filled.
         else if (E <= 64)
-            rc = tiles32 >= 1024 ? launch_gate<2, 2, 256, true>(xv, wv, logits, T, H, E, st)
+            rc = tiles32 >= 1024 ? launch_gate<4, 2, 128, false, true>(xv, wv, logits, T, H, E, st)
                                  : launch_gate<1, 2, 512, true>(xv, wv, logits, T, H, E, st);
         else if (E <= 128)
-            rc = launch_gate<1, 4, 256, true>(xv, wv, logits, T, H, E, st);
+            rc = tiles32 >= 1024 ? launch_gate<4, 4, 64, false, true>(xv, wv, logits, T, H, E, st)
+                                 : launch_gate<1, 4, 256, true>(xv, wv, logits, T, H, E, st);
         else
-            rc = launch_gate<1, 8, 128, false>(xv, wv, logits, T, H, E, st);
+            rc = tiles32 >= 1024 ? launch_gate<4, 8, 64, false, true>(xv, wv, logits, T, H, E, st)
+                                 : launch_gate<1, 8, 128, false>(xv, wv, logits, T, H, E, st);
         if (rc) return rc;
     } else {
         hipLaunchKernelGGL(gate_f32_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, st,

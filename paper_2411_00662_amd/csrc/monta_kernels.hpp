@@ -1053,19 +1053,23 @@ struct GateTile {
     static constexpr int kLoads = (32 * (MT + NT) * kPiecesPerRow + kGateThreads - 1) / kGateThreads;
     static constexpr int kTiles = MT * NT;
     // partial tiles of several waves side by side in 64 KiB; waves sharing a slot add one after the other
-    static constexpr int kSlots = (16 / kTiles) < kGateWaves ? (16 / kTiles) : kGateWaves;
+    static constexpr int kSlots = kTiles > 16 ? 1 : (16 / kTiles) < kGateWaves ? (16 / kTiles) : kGateWaves;
     static constexpr int kRounds = kGateWaves / kSlots;
-    static_assert(kSlots >= 1 && kSlots * kRounds == kGateWaves, "gate reduction: waves must fill the slots evenly");
-    static_assert((KS & (KS - 1)) == 0 && KS >= 128, "gate: KS must be a power of two, at least one k-slice per wave");
-    static constexpr size_t lds_bytes(int E)
+    static_assert(kSlots * kRounds == kGateWaves, "gate reduction: waves must fill the slots evenly");
+    static_assert((KS & (KS - 1)) == 0 && KS >= 64, "gate: KS must be a power of two");
+    // `reduce`: the kernel variant that adds the waves' partial tiles through LDS at the end
+    static constexpr size_t lds_bytes(int E, bool reduce)
     {
-        const size_t tile = (size_t)(kTokens + E) * kRowStride, red = (size_t)kSlots * kTiles * 4096;
+        const size_t tile = (size_t)(kTokens + E) * kRowStride, red = reduce ? (size_t)kSlots * kTiles * 4096 : 0;
         return tile > red ? tile : red;
     }
 };
 
-// DEEP: two tiles in flight instead of one (not where the accumulators leave no registers for it)
-template <int MT, int NT, int KS, bool DEEP>
+// DEEP: two tiles in flight instead of one (not where the accumulators leave no registers for it).
+// SPLIT (needs MT*NT = number of waves): instead of dealing the k-slices, every wave owns one 32x32 output tile
+// and walks all k-slices of it: one accumulator tile per wave, which leaves registers for larger tiles in
+// flight, and no reduction across waves at the end.
+template <int MT, int NT, int KS, bool DEEP, bool SPLIT>
 __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
                                                                  float *__restrict__ logits, int64_t T, int H, int E)
 {
@@ -1112,12 +1116,34 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const u32x4 *__
         __syncthreads();
     };
 
-    f32x16 acc[G::kTiles];
+    // SPLIT: wave v owns column tile v % NT and the row tiles v / NT + i * (waves / NT)
+    constexpr int kPerWave = G::kTiles / kGateWaves, kRowTileStep = kGateWaves / NT;
+    static_assert(!SPLIT || (kGateWaves % NT == 0 && kPerWave >= 1 && kPerWave * kRowTileStep == MT),
+                  "gate: the output tiles must divide evenly among the waves");
+    constexpr int kAcc = SPLIT ? kPerWave : G::kTiles;
+    f32x16 acc[kAcc];
 #pragma unroll
-    for (int i = 0; i < G::kTiles; ++i)
+    for (int i = 0; i < kAcc; ++i)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
     auto multiply = [&]() {
+        if constexpr (SPLIT) {
+            const int n = (wave % NT) * 32 + m;
+            const unsigned char *pa = gate_lds + (size_t)((wave / NT) * 32 + m) * G::kRowStride + g * 16;
+            const unsigned char *pb = gate_lds + (size_t)(G::kTokens + (n < E ? n : 0)) * G::kRowStride + g * 16;
+#pragma unroll 4
+            for (int ks = 0; ks < KS / 16; ++ks) {
+                bf16x8 b = *reinterpret_cast<const bf16x8 *>(pb + ks * 32);
+                if (n >= E) b = __builtin_bit_cast(bf16x8, zero);
+#pragma unroll
+                for (int i = 0; i < kAcc; ++i) {
+                    const bf16x8 a =
+                        *reinterpret_cast<const bf16x8 *>(pa + (size_t)i * kRowTileStep * 32 * G::kRowStride + ks * 32);
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+                }
+            }
+            return;
+        }
         for (int ks = wave; ks < KS / 16; ks += kGateWaves) {
             const int off = ks * 32 + g * 16;
             bf16x8 a[MT], b[NT];
@@ -1163,6 +1189,18 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const u32x4 *__
         }
     }
 
+    if constexpr (SPLIT) {
+        // element j of this lane: row (j/4)*8 + g*4 + j%4, column m of the wave's own tile
+        const int n = (wave % NT) * 32 + m;
+#pragma unroll
+        for (int i = 0; i < kAcc; ++i)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int64_t t = t0 + (wave / NT + i * kRowTileStep) * 32 + (j >> 2) * 8 + g * 4 + (j & 3);
+                if (t < T && n < E) logits[t * E + n] = acc[i][j];
+            }
+        return;
+    }
     // partial tiles -> LDS [slot][tile][row][col]
     float *red = reinterpret_cast<float *>(gate_lds);
     const int slot = wave % G::kSlots, round = wave / G::kSlots;
@@ -1175,7 +1213,7 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const u32x4 *__
                 for (int j = 0; j < 16; ++j) {
                     const int row = (j >> 2) * 8 + g * 4 + (j & 3);
                     float *q = red + ((slot * G::kTiles + i) * 32 + row) * 32 + m;
-                    *q = (r == 0) ? acc[i][j] : *q + acc[i][j];
+                    *q = (r == 0) ? acc[i % kAcc][j] : *q + acc[i % kAcc][j];
                 }
         }
         __syncthreads();

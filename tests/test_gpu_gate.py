@@ -65,7 +65,10 @@ SHAPES = [(1, 8, 1), (31, 64, 7), (100, 200, 8), (257, 1032, 33), (64, 4096, 64)
           (1000, 4096, 8), (33, 8, 129),
           # at most 8 experts and whole 64-element quarters: the persistent whole-row kernel, one and two chunks per row,
           # quarters that are not powers of two, fewer MFMA steps than waves, more groups than workgroups
-          (70, 8192, 8), (45, 7168, 3), (19, 1088, 5), (300, 2048, 2), (64, 128, 8), (9, 4160, 1), (5000, 256, 6)]
+          (70, 8192, 8), (45, 7168, 3), (19, 1088, 5), (300, 2048, 2), (64, 128, 8), (9, 4160, 1), (5000, 256, 6),
+          # many tokens and more than 32 experts: 128-token workgroups, a wave per output tile (one, two and four
+          # tiles per wave), ragged last workgroup, hidden sizes that are not whole steps
+          (32773, 64, 64), (32800, 72, 100), (32769, 136, 200), (33000, 200, 33)]
 
 
 @pytest.mark.parametrize("dtype", [BF16, FP32])
