@@ -242,6 +242,43 @@ def volume(pl: Plan, tp: int, S: int, row_bytes: int):
     return unit_bytes, dest_bytes, slice_bytes
 
 
+def expert_ranges(pl: "Plan", tp: int, S: int, slice: int = -1):
+    """Row ranges [lo, hi) of every expert in the expert-major buffer: the whole kept segment, or the part
+    of it that the tokens of one slice fill (token order inside a segment makes that one contiguous run)."""
+    E = pl.kept.shape[0]
+    lo = np.asarray(pl.offsets[:E], np.int32).copy()
+    hi = (lo + np.asarray(pl.kept, np.int32)).astype(np.int32)
+    if slice >= 0:
+        ub = np.asarray(pl.unit_base, np.int32).reshape(S * tp, E)
+        lo = ub[slice * tp].copy()
+        if slice + 1 < S:
+            hi = ub[(slice + 1) * tp].copy()
+    return np.ascontiguousarray(lo), np.ascontiguousarray(hi)
+
+
+def expert(x_final: np.ndarray, w: np.ndarray, seg_lo: np.ndarray, seg_hi: np.ndarray, y: np.ndarray | None = None,
+           only_rows=None) -> np.ndarray:
+    """One linear layer per expert on the expert-major buffer: y[r] = x_final[r] @ w[e].T for rows r of expert e's
+    range.  x_final [rows, H], w [E, N, H], same dtype (float32 or uint16 bf16 bits); y [rows, N] is created
+    zero-filled if not given; rows outside every range stay as they are."""
+    x_final = np.ascontiguousarray(x_final)
+    w = np.ascontiguousarray(w)
+    if x_final.dtype != w.dtype or x_final.dtype not in (np.float32, np.uint16) or w.ndim != 3 or w.shape[2] != x_final.shape[1]:
+        raise ValueError("oracle expert: x_final [rows,H] and w [E,N,H] must share dtype (float32 or uint16) and H")
+    E, N, H = w.shape
+    if y is None:
+        y = np.zeros((x_final.shape[0], N), x_final.dtype)
+    assert y.flags.c_contiguous and y.dtype == x_final.dtype and y.shape == (x_final.shape[0], N)
+    lo = np.ascontiguousarray(seg_lo, np.int32)
+    hi = np.ascontiguousarray(seg_hi, np.int32)
+    assert lo.shape == (E,) and hi.shape == (E,) and int(hi.max(initial=0)) <= x_final.shape[0]
+    rows = None if only_rows is None else np.ascontiguousarray(only_rows, np.int32)
+    rc = _load().monta_oracle_expert(E, H, N, 0 if x_final.dtype == np.float32 else 1, _p(lo), _p(hi), _p(x_final), _p(w),
+                                     _p(y), None if rows is None else _p(rows), ctypes.c_int64(0 if rows is None else rows.size))
+    _check(rc, "expert")
+    return y
+
+
 @dataclass
 class Result:
     topk_idx: np.ndarray

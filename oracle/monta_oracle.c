@@ -398,6 +398,50 @@ int monta_oracle_combine_staged(int64_t t0, int64_t t1, int H, int k, int dtype,
                                 (char *)out + t0 * H * bpe);
 }
 
+/* ----------------------------------------------------------------- expert */
+
+/* Expert computation (section "Expert Parallel": between Dispatch and Combine every expert processes
+ * the tokens that were grouped to it; section "Pipelining": it may start once the D2D copies of the
+ * chunks it needs are done).  One linear layer per expert stands in for the expert network: for
+ * expert e and every row r in [seg_lo[e], seg_hi[e]) of the expert-major buffer,
+ *   y[r][n] = sum_k x_final[r][k] * w[e][n][k],   w [E][N][H] (one row of H inputs per output feature),
+ * products exact in double, summed over k ascending in double, rounded once to the activation type.
+ * Rows outside every range are left untouched.  If only_rows is not NULL only the listed rows are
+ * evaluated (rows outside every range are skipped). */
+int monta_oracle_expert(int E, int H, int N, int dtype, const int32_t *seg_lo, const int32_t *seg_hi,
+                        const void *x_final, const void *w, void *y, const int32_t *only_rows, int64_t n_only)
+{
+    if (E < 1 || H < 1 || N < 1 || (dtype != 0 && dtype != 1) || n_only < 0) return ORACLE_BAD_ARG;
+    const int64_t count = only_rows ? n_only : -1;
+    for (int e = 0; e < E; ++e) {
+        const int64_t lo = seg_lo[e], hi = seg_hi[e];
+        if (hi < lo || lo < 0) return ORACLE_BAD_ARG;
+        const int64_t span = only_rows ? count : hi - lo;
+        for (int64_t i = 0; i < span; ++i) {
+            const int64_t r = only_rows ? only_rows[i] : lo + i;
+            if (r < lo || r >= hi) continue;
+            for (int n = 0; n < N; ++n) {
+                const int64_t wbase = ((int64_t)e * N + n) * H;
+                double acc = 0.0;
+                for (int k = 0; k < H; ++k) {
+                    double a, b;
+                    if (dtype == 0) {
+                        a = (double)((const float *)x_final)[r * H + k];
+                        b = (double)((const float *)w)[wbase + k];
+                    } else {
+                        a = bf16_to_double(((const uint16_t *)x_final)[r * H + k]);
+                        b = bf16_to_double(((const uint16_t *)w)[wbase + k]);
+                    }
+                    acc += a * b;
+                }
+                if (dtype == 0) ((float *)y)[r * N + n] = (float)acc;
+                else ((uint16_t *)y)[r * N + n] = double_to_bf16(acc);
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
 /* ----------------------------------------------------------------- volume */
 
 /* Byte accounting of the exchange (Eq. 3 traffic I = b*s*h*BPE; Eq. 8-10 per-chunk

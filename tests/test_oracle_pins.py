@@ -163,6 +163,87 @@ def test_gate_projection_is_a_matrix_product(dtype):
     np.testing.assert_array_equal(oracle.gate(xi_in, oh_in), xi[:, [5, 63, 0]])
 
 
+# ------------------------------------------------------------------- expert
+
+def _expert_case(dtype, cf=0.6, seed=4):
+    w = Workload("ex", 96, 64, dtype, 6, 2, 3, 2, 2, cf)
+    logits, x = workloads.make_inputs(w, seed=seed)
+    ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor)
+    return w, ref
+
+
+@pytest.mark.parametrize("dtype", [FP32, BF16])
+def test_expert_layer_is_a_matrix_product_per_segment(dtype):
+    w, ref = _expert_case(dtype)
+    pl = ref.plan
+    assert 0 < pl.R < w.tokens * w.top_k and pl.kept.min() > 0
+    we = workloads.make_expert_weights(w, n_out=40, seed=1)
+    lo, hi = oracle.expert_ranges(pl, w.tp, w.slices)
+    canary = np.float32(7.0) if dtype == FP32 else np.uint16(0x4123)
+    y = np.full((pl.R + 3, 40), canary, dtype=ref.final.dtype)
+    xf = np.concatenate([ref.final[:pl.R], np.zeros((3, w.hidden), ref.final.dtype)])
+    oracle.expert(xf, we, lo, hi, y)
+    as64 = (lambda a: a.astype(np.float64)) if dtype == FP32 else (lambda a: workloads.bf16_bits_to_f32(a).astype(np.float64))
+    assert np.all(y[pl.R:] == canary)                               # rows of no expert are not touched
+    for e in range(w.experts):
+        seg = slice(int(pl.offsets[e]), int(pl.offsets[e] + pl.kept[e]))
+        want = as64(xf[seg]) @ as64(we[e]).T                         # library routine, its own summation order
+        got = as64(y[seg])
+        ulp = ulp32(want) if dtype == FP32 else np.maximum(np.abs(want), 1e-30) * 2.0 ** -7
+        assert np.all(np.abs(got - want) <= 0.5000001 * ulp + 1e-12), e
+    # power-of-two multiples of the identity: y = 2^e * x exactly, so a row handed to the wrong expert shows
+    eye = np.stack([np.eye(w.hidden, dtype=np.float32) * np.float32(2.0 ** e) for e in range(w.experts)])
+    eye_in = eye if dtype == FP32 else workloads.f32_to_bf16_bits(eye)
+    y2 = oracle.expert(ref.final[:pl.R], eye_in, lo, hi)
+    for e in range(w.experts):
+        seg = slice(int(pl.offsets[e]), int(pl.offsets[e] + pl.kept[e]))
+        np.testing.assert_array_equal(as64(y2[seg]), as64(ref.final[seg]) * 2.0 ** e)
+
+
+def test_expert_layer_by_slices_and_by_sampled_rows():
+    w, ref = _expert_case(BF16)
+    pl = ref.plan
+    we = workloads.make_expert_weights(w, seed=2)
+    lo, hi = oracle.expert_ranges(pl, w.tp, w.slices)
+    whole = oracle.expert(ref.final[:pl.R], we, lo, hi)
+    # the slices' ranges tile every segment in order, and computing slice by slice gives the same buffer
+    parts = np.zeros_like(whole)
+    covered = np.zeros(pl.R, np.int32)
+    prev_hi = lo.copy()
+    for j in range(w.slices):
+        lj, hj = oracle.expert_ranges(pl, w.tp, w.slices, j)
+        np.testing.assert_array_equal(lj, prev_hi)
+        prev_hi = hj
+        for e in range(w.experts):
+            covered[lj[e]:hj[e]] += 1
+            # rows of slice j in segment e are exactly the kept pairs of e whose token lies in slice j
+            toks = np.nonzero((ref.topk_idx == e).any(axis=1))[0]
+            pos = np.array([ref.plan.pos_final[t, list(ref.topk_idx[t]).index(e)] for t in toks])
+            in_slice = (toks // (w.tokens // w.slices) == j) & (pos >= 0)
+            assert sorted(pos[in_slice]) == list(range(lj[e], hj[e]))
+        oracle.expert(ref.final[:pl.R], we, lj, hj, parts)
+    np.testing.assert_array_equal(prev_hi, hi)
+    assert np.all(covered == 1)
+    np.testing.assert_array_equal(parts, whole)
+    # a sample of rows: the same values on those rows, nothing else written
+    rows = np.array([0, 5, pl.R - 1, int(pl.offsets[3])], np.int32)
+    some = oracle.expert(ref.final[:pl.R], we, lo, hi, only_rows=rows)
+    np.testing.assert_array_equal(some[rows], whole[rows])
+    mask = np.ones(pl.R, bool)
+    mask[rows] = False
+    assert not some[mask].any()
+
+
+def test_identity_expert_weights_give_the_identity_expert_path():
+    w, ref = _expert_case(BF16, cf=0.0)
+    pl = ref.plan
+    eye = workloads.f32_to_bf16_bits(np.stack([np.eye(w.hidden, dtype=np.float32)] * w.experts))
+    lo, hi = oracle.expert_ranges(pl, w.tp, w.slices)
+    y = oracle.expert(ref.final[:pl.R], eye, lo, hi)
+    np.testing.assert_array_equal(y, ref.final[:pl.R])
+    np.testing.assert_array_equal(oracle.combine(y, ref.gates, pl.pos_final), ref.out)
+
+
 # --------------------------------------------------------------------- plan
 
 def test_capacity_formula():

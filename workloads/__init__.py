@@ -132,3 +132,13 @@ def make_gate_weights(w: Workload, seed: int | None = None) -> np.ndarray:
     rng = np.random.default_rng(10_000 + (w.seed if seed is None else seed))
     wg = (rng.standard_normal((w.experts, w.hidden), dtype=np.float32) / np.float32(np.sqrt(w.hidden))).astype(np.float32)
     return f32_to_bf16_bits(wg) if w.dtype == BF16 else np.ascontiguousarray(wg)
+
+
+def make_expert_weights(w: Workload, n_out: int | None = None, seed: int | None = None) -> np.ndarray:
+    """Random-init weights of one linear layer per expert, [E, N, H] (a row of H inputs per output feature; N = H
+    unless given), standard normals scaled by 1/sqrt(H), in the workload's activation type."""
+    n_out = w.hidden if n_out is None else n_out
+    rng = np.random.default_rng(20_000 + (w.seed if seed is None else seed))
+    we = rng.standard_normal((w.experts, n_out, w.hidden), dtype=np.float32)
+    we *= np.float32(1.0 / np.sqrt(w.hidden))
+    return f32_to_bf16_bits(we) if w.dtype == BF16 else np.ascontiguousarray(we)
