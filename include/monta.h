@@ -131,6 +131,20 @@ int monta_ws_init(const monta_cfg *cfg, void *ws, void *stream);
  * validated); needs no workspace.  Nothing is owned or kept; the work is enqueued on `stream`. */
 int monta_gate(const monta_cfg *cfg, const void *x, const void *w_gate, float *logits, void *stream);
 
+/* Expert computation on the expert-major buffer (section "Expert Parallel": between Dispatch and Combine every
+ * expert processes the tokens grouped to it; section "Pipelining": the expert computation waits for the D2D
+ * copies of the chunks it reads).  One linear layer per expert stands in for the expert network:
+ *   y[r][n] = sum_h x_final[r][h] * w_exp[e][n][h]   for every kept row r of expert e,
+ * x_final [max_rows][H] (the FINAL buffer, compact or padded layout), w_exp [E][out_features][H] (one row of H
+ * inputs per output feature), y [max_rows][out_features], all in cfg->dtype, device pointers, 16-byte aligned;
+ * out_features a multiple of 8 (bf16) or 4 (fp32).  slice = -1: all kept rows; slice = j: only the rows that
+ * slice j's tokens fill (one contiguous run per expert), so the call can follow monta_regather(j) while later
+ * slices are still being moved.  Rows of no expert (and padding rows) are not written.  bf16 runs on the matrix
+ * cores with fp32 accumulation and one rounding to bf16; the order of the additions is fixed for a shape.
+ * Needs the tables written by monta_route on `ws`; enqueued on `stream`. */
+int monta_expert_linear(const monta_cfg *cfg, const void *x_final, const void *w_exp, int32_t out_features, void *y,
+                        const void *ws, int slice, void *stream);
+
 /* Routing + Permutation plan.  logits [T][E] fp32 -> topk_idx [T][k] int32 (slot 0
  * = strongest choice; ties go to the lower expert index; selection is on the raw
  * logits), gates [T][k] fp32 (evaluated in fp64, rounded once), and every plan
@@ -262,7 +276,8 @@ enum monta_kernel_id {
     MONTA_K_UNREGATHER_COMBINE = 9, /* co-scheduled grid of the return pipeline */
     MONTA_K_ALLGATHER = 10,
     MONTA_K_GATE = 11,      /* gate projection                                */
-    MONTA_K_COUNT = 12
+    MONTA_K_EXPERT = 12,    /* expert layer (grouped GEMM)                    */
+    MONTA_K_COUNT = 13
 };
 int monta_profile_enable(int on);
 int monta_profile_reset(void);

@@ -17,9 +17,9 @@ LIB_PATH = os.path.join(_PKG, "libmonta.so")
 
 FP32, BF16 = 0, 1
 (K_ROUTE, K_POSITIONS, K_PACK, K_REGATHER, K_PACK_REGATHER, K_COMBINE, K_COPY, K_PLAN_PACK, K_UNREGATHER,
- K_UNREGATHER_COMBINE, K_ALLGATHER, K_GATE) = range(12)
+ K_UNREGATHER_COMBINE, K_ALLGATHER, K_GATE, K_EXPERT) = range(13)
 KERNEL_NAMES = ["route_plan", "positions", "pack", "regather", "pack_regather", "combine", "copy", "plan_pack",
-                "unregather", "unregather_combine", "allgather", "gate"]
+                "unregather", "unregather_combine", "allgather", "gate", "expert"]
 
 
 class MontaError(RuntimeError):
@@ -68,7 +68,7 @@ class monta_plan_out(ctypes.Structure):
 
 
 # every symbol include/monta.h declares
-EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "monta_gate", "monta_route", "monta_dispatch",
+EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "monta_gate", "monta_expert_linear", "monta_route", "monta_dispatch",
            "monta_regather", "monta_dispatch_regather", "monta_route_dispatch_regather", "monta_combine", "monta_unregather", "monta_combine_staged",
            "monta_unregather_combine", "monta_allgather", "monta_set_pipeline_mode",
            "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
@@ -108,6 +108,7 @@ def lib() -> ctypes.CDLL:
         L.monta_get_cache_policy.argtypes = []
         L.monta_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.monta_gate.argtypes = [ctypes.POINTER(monta_cfg), vp, vp, vp, vp]
+        L.monta_expert_linear.argtypes = [ctypes.POINTER(monta_cfg), vp, vp, i32, vp, vp, i32, vp]
         L.monta_profile_enable.argtypes = [i32]
         L.monta_profile_reset.argtypes = []
         L.monta_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), i64p]
@@ -299,6 +300,15 @@ def monta_gate(cfg, x, w_gate, logits, stream=None):
     row = cfg.hidden * _bpe(cfg)
     _check(lib().monta_gate(ctypes.byref(cfg), _ptr(x, cfg.tokens * row, "x"), _ptr(w_gate, cfg.experts * row, "w_gate"),
                             _ptr(logits, cfg.tokens * cfg.experts * 4, "logits"), _stream(stream)), "monta_gate")
+
+
+def monta_expert_linear(cfg, x_final, w_exp, out_features: int, y, ws, slice: int = -1, stream=None):
+    L = monta_ws_layout_query(cfg)
+    bpe = _bpe(cfg)
+    _check(lib().monta_expert_linear(ctypes.byref(cfg), _ptr(x_final, L.max_rows * cfg.hidden * bpe, "x_final"),
+                                     _ptr(w_exp, cfg.experts * int(out_features) * cfg.hidden * bpe, "w_exp"),
+                                     int(out_features), _ptr(y, L.max_rows * int(out_features) * bpe, "y"),
+                                     _ptr(ws, L.ws_bytes, "ws"), int(slice), _stream(stream)), "monta_expert_linear")
 
 
 def monta_copy(dst, src, nbytes: int, stream=None):

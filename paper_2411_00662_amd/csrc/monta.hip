@@ -581,6 +581,59 @@ int monta_gate(const monta_cfg *cfg, const void *x, const void *w_gate, float *l
     return MONTA_OK;
 }
 
+int monta_expert_linear(const monta_cfg *cfg, const void *x_final, const void *w_exp, int32_t out_features, void *y,
+                        const void *ws, int slice, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (!x_final || !w_exp || !y || !ws) return MONTA_ERR_NULL;
+    if (misaligned(x_final, 16) || misaligned(w_exp, 16) || misaligned(y, 16) || misaligned(ws, 16)) return MONTA_ERR_ALIGN;
+    const Shape &s = g.s;
+    const int bpe = cfg->dtype == MONTA_BF16 ? 2 : 4;
+    if (out_features < 1 || ((int64_t)out_features * bpe) % 16 != 0) return MONTA_ERR_INVALID;
+    if (slice < -1 || slice >= s.S) return MONTA_ERR_INVALID;
+    if (x_final == y) return MONTA_ERR_INVALID;
+    PlanPtrs p = plan_ptrs(g, const_cast<void *>(ws));
+    ExpertArgs a;
+    a.E = s.E;
+    a.H = cfg->hidden;
+    a.N = out_features;
+    a.max_rows = s.max_rows;
+    // rows of expert e: its whole kept segment [offsets[e], offsets[e] + kept[e]), or the part of it filled by the
+    // slice's units, which starts at unit_base[first unit of the slice][e] and ends where the next slice's starts
+    a.lo = slice < 0 ? p.offsets : p.unit_base + (int64_t)slice * s.tp * s.E;
+    if (slice >= 0 && slice + 1 < s.S) {
+        a.hi_base = p.unit_base + (int64_t)(slice + 1) * s.tp * s.E;
+        a.hi_len = nullptr;
+    } else {
+        a.hi_base = p.offsets;
+        a.hi_len = p.kept;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // worst case of the rows in play: every pair of the slice's tokens kept
+    int64_t rows_bound = slice < 0 ? (int64_t)s.max_rows : std::min<int64_t>(s.max_rows, (int64_t)(s.T / s.S) * s.k);
+    ProfScope ps(MONTA_K_EXPERT, st);
+    if (cfg->dtype == MONTA_BF16) {
+        const int64_t row_tiles = (rows_bound + kExpBM - 1) / kExpBM + s.E;      // each expert may end in a ragged tile
+        const int64_t nct = (out_features + kExpBN - 1) / kExpBN;
+        const int64_t grid8 = (row_tiles * nct + kXcds - 1) / kXcds * kXcds;
+        if (grid8 > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
+        a.grid8 = (int32_t)grid8;
+        hipLaunchKernelGGL(expert_bf16_kernel, dim3((unsigned)grid8), dim3(kExpThreads), kExpLdsBytes, st,
+                           static_cast<const u32x4 *>(x_final), static_cast<const u32x4 *>(w_exp),
+                           static_cast<unsigned short *>(y), a);
+    } else {
+        a.grid8 = 0;
+        const int64_t blocks = ((int64_t)s.max_rows * out_features + 255) / 256;
+        if (blocks > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(expert_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const float *>(x_final),
+                           static_cast<const float *>(w_exp), static_cast<float *>(y), a);
+    }
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
 int monta_route(const monta_cfg *cfg, const float *logits, int32_t *topk_idx, float *gates, void *ws, void *stream)
 {
     Geometry g;

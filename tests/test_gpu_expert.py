@@ -1,0 +1,210 @@
+"""GPU parity of the expert layer (monta_expert_linear, a grouped GEMM over the expert-major buffer).
+
+Bar.  The oracle sums x[r][h] * w[e][n][h] over h in double and rounds once to the activation type; the kernel
+adds the same exact products in fp32 (matrix cores) in another order and rounds once.  Any order of H fp32
+additions of exact products is within H * 2^-24 * sum|x*w| of the true sum; the rounding to bf16 can then fall
+on the other side of a rounding boundary, one bf16 ulp (2^-7 relative at most).  With small-integer inputs every
+partial sum is an integer below 2^24, both sides hold the exact sum before the one rounding, and the results
+must agree bit for bit: that case pins every index of the kernel (row ranges, tiles, tails, expert of a row).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from workloads import BF16, FP32, Workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def m():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2411_00662_amd as mod
+    mod.binding.lib()
+    return mod
+
+
+def as64(a, dtype):
+    return (a if dtype == FP32 else workloads.bf16_bits_to_f32(a)).astype(np.float64)
+
+
+def to_act(a, dtype):
+    return np.ascontiguousarray(a, np.float32) if dtype == FP32 else workloads.f32_to_bf16_bits(a)
+
+
+def run_path(m, w, logits, x):
+    """Route + dispatch + regather on the GPU; returns the buffers and the oracle's view of the same inputs."""
+    import torch
+    cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm,
+                     w.padded)
+    b = m.alloc_buffers(cfg, logits, x, canary=0xA5)
+    m.monta_route_dispatch_regather(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, b.ws)
+    torch.cuda.synchronize()
+    ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm,
+                         padded=w.padded)
+    return cfg, b, ref
+
+
+def expert_gpu(m, cfg, b, we, n_out, slices=(-1,), canary=0x5A):
+    import torch
+    from paper_2411_00662_amd import buffers as bufs
+    wd = bufs.to_device_act(cfg, we.reshape(-1, we.shape[-1]))
+    L = m.monta_ws_layout_query(cfg)
+    y = torch.empty((L.max_rows + 1, n_out), dtype=b.final.dtype, device="cuda:0")     # one row of canary behind the buffer
+    y.view(torch.uint8).fill_(canary)
+    for j in slices:
+        m.monta_expert_linear(cfg, b.final, wd, n_out, y[:L.max_rows], b.ws, j)
+    torch.cuda.synchronize()
+    host = bufs.to_host_act(cfg, y)
+    assert np.all(host[L.max_rows].view(np.uint8) == canary), "monta_expert_linear wrote past the end of y"
+    return host[:L.max_rows], wd
+
+
+def check_untouched(y, pl, canary=0x5A):
+    """Rows of no expert's kept range keep the canary."""
+    mask = np.ones(y.shape[0], bool)
+    for e in range(pl.kept.shape[0]):
+        mask[int(pl.offsets[e]):int(pl.offsets[e] + pl.kept[e])] = False
+    assert np.all(y[mask].view(np.uint8) == canary)
+    return np.nonzero(~mask)[0]
+
+
+# tokens, hidden, experts, k, ep, tp, S, cf, out features, padded: ragged row tiles, two column tiles with a ragged
+# second one, hidden sizes that are not whole 64-element steps (and one shorter than a step), drops, an expert
+# layout with padding rows
+CASES = [
+    (300, 200, 6, 2, 3, 2, 2, 0.7, 264, 0),
+    (1000, 64, 4, 2, 2, 1, 4, 0.0, 512, 0),
+    (256, 24, 8, 1, 2, 2, 2, 0.0, 40, 0),
+    (640, 136, 5, 3, 1, 2, 2, 0.5, 256, 1),
+    (2048, 256, 2, 1, 2, 4, 2, 0.0, 8, 0),
+]
+
+
+@pytest.mark.parametrize("dtype", [BF16, FP32])
+@pytest.mark.parametrize("case", CASES)
+def test_expert_small_integers_bit_exact(m, case, dtype):
+    T, H, E, k, ep, tp, S, cf, N, padded = case
+    _say(f"expert ints {case} dtype={dtype}")
+    w = Workload("ex", T, H, dtype, E, k, ep, tp, S, cf, padded=padded)
+    logits = workloads.make_logits(w, seed=T + H)
+    rng = np.random.default_rng(H + N)
+    x = to_act(rng.integers(-4, 5, size=(T, H)).astype(np.float32), dtype)
+    we = to_act(rng.integers(-4, 5, size=(E, N, H)).astype(np.float32), dtype)
+    cfg, b, ref = run_path(m, w, logits, x)
+    pl = ref.plan
+    lo, hi = oracle.expert_ranges(pl, tp, S)
+    want = oracle.expert(ref.final, we, lo, hi)
+    got, _ = expert_gpu(m, cfg, b, we, N)
+    rows = check_untouched(got, pl)
+    np.testing.assert_array_equal(got[rows], want[rows])
+    # slice by slice, in any order, fills the same buffer
+    got2, _ = expert_gpu(m, cfg, b, we, N, slices=tuple(reversed(range(S))))
+    check_untouched(got2, pl)
+    np.testing.assert_array_equal(got2[rows], want[rows])
+    # one slice alone writes that slice's rows and nothing else
+    lj, hj = oracle.expert_ranges(pl, tp, S, 0)
+    got3, _ = expert_gpu(m, cfg, b, we, N, slices=(0,))
+    only = np.zeros(got3.shape[0], bool)
+    for e in range(E):
+        only[lj[e]:hj[e]] = True
+    np.testing.assert_array_equal(got3[np.nonzero(only)[0]], want[np.nonzero(only)[0]])
+    assert np.all(got3[~only].view(np.uint8) == 0x5A)
+
+
+@pytest.mark.parametrize("dtype", [BF16, FP32])
+@pytest.mark.parametrize("case", CASES[:4])
+def test_expert_normal_inputs_within_bound(m, case, dtype):
+    T, H, E, k, ep, tp, S, cf, N, padded = case
+    _say(f"expert normal {case} dtype={dtype}")
+    w = Workload("ex", T, H, dtype, E, k, ep, tp, S, cf, padded=padded)
+    logits, x = workloads.make_inputs(w, seed=7)
+    we = workloads.make_expert_weights(w, n_out=N, seed=7)
+    cfg, b, ref = run_path(m, w, logits, x)
+    pl = ref.plan
+    lo, hi = oracle.expert_ranges(pl, tp, S)
+    want = oracle.expert(ref.final, we, lo, hi)
+    got, wd = expert_gpu(m, cfg, b, we, N)
+    rows = check_untouched(got, pl)
+    for e in range(E):
+        seg = slice(int(pl.offsets[e]), int(pl.offsets[e] + pl.kept[e]))
+        mag = np.abs(as64(ref.final[seg], dtype)) @ np.abs(as64(we[e], dtype)).T
+        ref64 = as64(want[seg], dtype)
+        tol = H * 2.0 ** -24 * mag + (2.0 ** -24 if dtype == FP32 else 2.0 ** -7) * np.abs(ref64) + 1e-30
+        err = np.abs(as64(got[seg], dtype) - ref64)
+        assert np.all(err <= tol), f"expert {e}: max err/tol {np.max(err / tol):.3g}"
+    # repeatable bit for bit
+    again, _ = expert_gpu(m, cfg, b, we, N)
+    np.testing.assert_array_equal(again, got)
+
+
+def test_expert_identity_weights_reproduce_the_identity_expert_path(m):
+    """w[e] = I: y equals FINAL on the kept rows, and combine of y equals combine of FINAL."""
+    import torch
+    from paper_2411_00662_amd import buffers as bufs
+    w = Workload("ex-id", 1024, 256, BF16, 8, 2, 4, 2, 2, 1.0)
+    logits, x = workloads.make_inputs(w, seed=3)
+    eye = workloads.f32_to_bf16_bits(np.stack([np.eye(w.hidden, dtype=np.float32)] * w.experts))
+    cfg, b, ref = run_path(m, w, logits, x)
+    got, _ = expert_gpu(m, cfg, b, eye, w.hidden)
+    R = ref.plan.R
+    np.testing.assert_array_equal(got[:R], ref.final[:R])
+    y = bufs.to_device_act(cfg, got)
+    m.monta_combine(cfg, y, b.gates, b.out, b.ws)
+    torch.cuda.synchronize()
+    same = np.all(b.gates.cpu().numpy() == ref.gates, axis=1)
+    np.testing.assert_array_equal(bufs.to_host_act(cfg, b.out)[same], ref.out[same])
+
+
+def test_expert_skips_an_expert_nobody_chose(m):
+    w = Workload("ex-empty", 512, 128, BF16, 4, 1, 2, 2, 2, 0.0)
+    logits, x = workloads.make_inputs(w, seed=5)
+    logits[:, 2] = -50.0                                  # expert 2 is never chosen
+    we = workloads.make_expert_weights(w, n_out=64, seed=5)
+    cfg, b, ref = run_path(m, w, logits, x)
+    pl = ref.plan
+    assert pl.kept[2] == 0
+    lo, hi = oracle.expert_ranges(pl, w.tp, w.slices)
+    want = oracle.expert(ref.final, we, lo, hi)
+    got, _ = expert_gpu(m, cfg, b, we, 64)
+    rows = check_untouched(got, pl)
+    err = np.abs(as64(got[rows], BF16) - as64(want[rows], BF16))
+    assert np.all(err <= 2.0 ** -6 * np.abs(as64(want[rows], BF16)) + 1e-6)
+
+
+@pytest.mark.parametrize("name", ["mixtral", "2x70b"])
+def test_expert_named_workloads_full_size(m, name):
+    """Full-size launch (N = H); the oracle recomputes a sample of rows, among them each segment's first and last."""
+    w = workloads.CONFIGS[name]
+    _say(f"expert workload {name}")
+    logits, x = workloads.make_inputs(w)
+    we = workloads.make_expert_weights(w)
+    cfg, b, ref = run_path(m, w, logits, x)
+    pl = ref.plan
+    got, _ = expert_gpu(m, cfg, b, we, w.hidden)
+    check_untouched(got, pl)
+    lo, hi = oracle.expert_ranges(pl, w.tp, w.slices)
+    rng = np.random.default_rng(9)
+    rows = [int(r) for e in range(w.experts) if hi[e] > lo[e] for r in (lo[e], hi[e] - 1)]
+    rows += [int(r) for r in rng.integers(0, pl.R, size=max(4, 24 - len(rows)))]
+    rows = np.unique(np.array(rows, np.int32))
+    want = oracle.expert(ref.final, we, lo, hi, only_rows=rows)
+    expert_of = np.searchsorted(np.asarray(pl.offsets[1:w.experts + 1]), rows, side="right")
+    for r, e in zip(rows, expert_of):
+        mag = np.abs(as64(ref.final[r], BF16)) @ np.abs(as64(we[e], BF16)).T
+        ref64 = as64(want[r], BF16)
+        tol = w.hidden * 2.0 ** -24 * mag + 2.0 ** -7 * np.abs(ref64) + 1e-30
+        err = np.abs(as64(got[r], BF16) - ref64)
+        assert np.all(err <= tol), f"row {r} expert {e}: max err/tol {np.max(err / tol):.3g}"
+        # the typical error is rounding to bf16 only: a dropped or doubled step of the hidden axis is not
+        assert np.sqrt(np.mean(err ** 2)) <= 2.0 ** -8 * np.sqrt(np.mean(ref64 ** 2))
