@@ -145,6 +145,18 @@ int monta_gate(const monta_cfg *cfg, const void *x, const void *w_gate, float *l
 int monta_expert_linear(const monta_cfg *cfg, const void *x_final, const void *w_exp, int32_t out_features, void *y,
                         const void *ws, int slice, void *stream);
 
+/* Routing, the slice pipeline and the expert layer in one call (section "Pipelining": the expert computation needs
+ * the D2D copies of the chunks it reads; overlapping it with the remaining copies is what the paper leaves as future
+ * work).  overlap = 0: monta_route_dispatch_regather, then monta_expert_linear on all rows, on `stream`.
+ * overlap = 1: as soon as the regather of slice j is done, the expert layer of slice j's rows starts on a second
+ * stream of the library (default priority) while `stream` goes on packing and regathering slice j+1; the call
+ * returns with `stream` waiting for the last expert launch.  Either way y holds the same values (a row's result
+ * does not depend on which launch computed it).  Arguments as in monta_route_dispatch_regather and
+ * monta_expert_linear; y must not alias x, stage or final_. */
+int monta_route_dispatch_expert(const monta_cfg *cfg, const float *logits, const void *x, int32_t *topk_idx, float *gates,
+                                void *stage, void *final_, const void *w_exp, int32_t out_features, void *y, void *ws,
+                                int overlap, void *stream);
+
 /* Routing + Permutation plan.  logits [T][E] fp32 -> topk_idx [T][k] int32 (slot 0
  * = strongest choice; ties go to the lower expert index; selection is on the raw
  * logits), gates [T][k] fp32 (evaluated in fp64, rounded once), and every plan

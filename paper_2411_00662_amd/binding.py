@@ -68,7 +68,7 @@ class monta_plan_out(ctypes.Structure):
 
 
 # every symbol include/monta.h declares
-EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "monta_gate", "monta_expert_linear", "monta_route", "monta_dispatch",
+EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "monta_gate", "monta_expert_linear", "monta_route_dispatch_expert", "monta_route", "monta_dispatch",
            "monta_regather", "monta_dispatch_regather", "monta_route_dispatch_regather", "monta_combine", "monta_unregather", "monta_combine_staged",
            "monta_unregather_combine", "monta_allgather", "monta_set_pipeline_mode",
            "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
@@ -109,6 +109,7 @@ def lib() -> ctypes.CDLL:
         L.monta_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.monta_gate.argtypes = [ctypes.POINTER(monta_cfg), vp, vp, vp, vp]
         L.monta_expert_linear.argtypes = [ctypes.POINTER(monta_cfg), vp, vp, i32, vp, vp, i32, vp]
+        L.monta_route_dispatch_expert.argtypes = [ctypes.POINTER(monta_cfg), vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp]
         L.monta_profile_enable.argtypes = [i32]
         L.monta_profile_reset.argtypes = []
         L.monta_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), i64p]
@@ -309,6 +310,20 @@ def monta_expert_linear(cfg, x_final, w_exp, out_features: int, y, ws, slice: in
                                      _ptr(w_exp, cfg.experts * int(out_features) * cfg.hidden * bpe, "w_exp"),
                                      int(out_features), _ptr(y, L.max_rows * int(out_features) * bpe, "y"),
                                      _ptr(ws, L.ws_bytes, "ws"), int(slice), _stream(stream)), "monta_expert_linear")
+
+
+def monta_route_dispatch_expert(cfg, logits, x, topk_idx, gates, stage, final, w_exp, out_features: int, y, ws,
+                                overlap: int = 1, stream=None):
+    L = monta_ws_layout_query(cfg)
+    bpe = _bpe(cfg)
+    row = cfg.hidden * bpe
+    T, k = cfg.tokens, cfg.top_k
+    _check(lib().monta_route_dispatch_expert(
+        ctypes.byref(cfg), _ptr(logits, T * cfg.experts * 4, "logits"), _ptr(x, T * row, "x"),
+        _ptr(topk_idx, T * k * 4, "topk_idx"), _ptr(gates, T * k * 4, "gates"), _ptr(stage, L.max_rows * row, "stage"),
+        _ptr(final, L.max_rows * row, "final"), _ptr(w_exp, cfg.experts * int(out_features) * row, "w_exp"),
+        int(out_features), _ptr(y, L.max_rows * int(out_features) * bpe, "y"), _ptr(ws, L.ws_bytes, "ws"), int(overlap),
+        _stream(stream)), "monta_route_dispatch_expert")
 
 
 def monta_copy(dst, src, nbytes: int, stream=None):

@@ -466,6 +466,27 @@ int launch_gate_small_any(const u32x4 *x, const u32x4 *w, float *logits, int64_t
     return 1;
 }
 
+template <int BM, int BN>
+int launch_expert(const void *x_final, const void *w_exp, void *y, ExpertArgs a, int64_t rows_bound, hipStream_t st)
+{
+    using G = ExpertTile<BM, BN>;
+    static std::atomic<int> lds_opt_in{0};
+    if (G::kLdsBytes > 48 * 1024 && !lds_opt_in.load()) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(expert_bf16_kernel<BM, BN>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, G::kLdsBytes));
+        lds_opt_in.store(1);
+    }
+    const int64_t row_tiles = (rows_bound + BM - 1) / BM + a.E;      // each expert may end in a ragged tile
+    const int64_t nct = (a.N + BN - 1) / BN;
+    const int64_t grid8 = (row_tiles * nct + kXcds - 1) / kXcds * kXcds;
+    if (grid8 > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
+    a.grid8 = (int32_t)grid8;
+    hipLaunchKernelGGL((expert_bf16_kernel<BM, BN>), dim3((unsigned)grid8), dim3(kExpThreads), G::kLdsBytes, st,
+                       static_cast<const u32x4 *>(x_final), static_cast<const u32x4 *>(w_exp),
+                       static_cast<unsigned short *>(y), a);
+    return MONTA_OK;
+}
+
 int launch_route(const Geometry &g, const PlanPtrs &p, const float *logits, int32_t *topk_idx, float *gates,
                  hipStream_t st)
 {
@@ -498,6 +519,56 @@ int check_route_ptrs(const float *logits, const int32_t *topk_idx, const float *
 }
 
 }  // namespace
+
+int check_expert_args(const monta_cfg *cfg, const Geometry &g, const void *x_final, const void *w_exp, int32_t out_features,
+                      const void *y, const void *ws, int slice)
+{
+    if (!x_final || !w_exp || !y || !ws) return MONTA_ERR_NULL;
+    if (misaligned(x_final, 16) || misaligned(w_exp, 16) || misaligned(y, 16) || misaligned(ws, 16)) return MONTA_ERR_ALIGN;
+    const int bpe = cfg->dtype == MONTA_BF16 ? 2 : 4;
+    if (out_features < 1 || ((int64_t)out_features * bpe) % 16 != 0) return MONTA_ERR_INVALID;
+    if (slice < -1 || slice >= g.s.S) return MONTA_ERR_INVALID;
+    if (x_final == y) return MONTA_ERR_INVALID;
+    return MONTA_OK;
+}
+
+int launch_expert_layer(const monta_cfg *cfg, const Geometry &g, const void *x_final, const void *w_exp, int32_t out_features,
+                        void *y, const void *ws, int slice, hipStream_t st)
+{
+    const Shape &s = g.s;
+    int rc = MONTA_OK;
+    PlanPtrs p = plan_ptrs(g, const_cast<void *>(ws));
+    ExpertArgs a;
+    a.E = s.E;
+    a.H = cfg->hidden;
+    a.N = out_features;
+    a.max_rows = s.max_rows;
+    // rows of expert e: its whole kept segment [offsets[e], offsets[e] + kept[e]), or the part of it filled by the
+    // slice's units, which starts at unit_base[first unit of the slice][e] and ends where the next slice's starts
+    a.lo = slice < 0 ? p.offsets : p.unit_base + (int64_t)slice * s.tp * s.E;
+    if (slice >= 0 && slice + 1 < s.S) {
+        a.hi_base = p.unit_base + (int64_t)(slice + 1) * s.tp * s.E;
+        a.hi_len = nullptr;
+    } else {
+        a.hi_base = p.offsets;
+        a.hi_len = p.kept;
+    }
+    // worst case of the rows in play: every pair of the slice's tokens kept
+    int64_t rows_bound = slice < 0 ? (int64_t)s.max_rows : std::min<int64_t>(s.max_rows, (int64_t)(s.T / s.S) * s.k);
+    ProfScope ps(MONTA_K_EXPERT, st);
+    if (cfg->dtype == MONTA_BF16) {
+        rc = launch_expert<128, 256>(x_final, w_exp, y, a, rows_bound, st);
+        if (rc) return rc;
+    } else {
+        a.grid8 = 0;
+        const int64_t blocks = ((int64_t)s.max_rows * out_features + 255) / 256;
+        if (blocks > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(expert_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const float *>(x_final),
+                           static_cast<const float *>(w_exp), static_cast<float *>(y), a);
+    }
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
 
 extern "C" {
 
@@ -587,50 +658,49 @@ int monta_expert_linear(const monta_cfg *cfg, const void *x_final, const void *w
     Geometry g;
     int rc = validate(cfg, &g);
     if (rc) return rc;
-    if (!x_final || !w_exp || !y || !ws) return MONTA_ERR_NULL;
-    if (misaligned(x_final, 16) || misaligned(w_exp, 16) || misaligned(y, 16) || misaligned(ws, 16)) return MONTA_ERR_ALIGN;
-    const Shape &s = g.s;
-    const int bpe = cfg->dtype == MONTA_BF16 ? 2 : 4;
-    if (out_features < 1 || ((int64_t)out_features * bpe) % 16 != 0) return MONTA_ERR_INVALID;
-    if (slice < -1 || slice >= s.S) return MONTA_ERR_INVALID;
-    if (x_final == y) return MONTA_ERR_INVALID;
-    PlanPtrs p = plan_ptrs(g, const_cast<void *>(ws));
-    ExpertArgs a;
-    a.E = s.E;
-    a.H = cfg->hidden;
-    a.N = out_features;
-    a.max_rows = s.max_rows;
-    // rows of expert e: its whole kept segment [offsets[e], offsets[e] + kept[e]), or the part of it filled by the
-    // slice's units, which starts at unit_base[first unit of the slice][e] and ends where the next slice's starts
-    a.lo = slice < 0 ? p.offsets : p.unit_base + (int64_t)slice * s.tp * s.E;
-    if (slice >= 0 && slice + 1 < s.S) {
-        a.hi_base = p.unit_base + (int64_t)(slice + 1) * s.tp * s.E;
-        a.hi_len = nullptr;
-    } else {
-        a.hi_base = p.offsets;
-        a.hi_len = p.kept;
-    }
+    if ((rc = check_expert_args(cfg, g, x_final, w_exp, out_features, y, ws, slice))) return rc;
+    return launch_expert_layer(cfg, g, x_final, w_exp, out_features, y, ws, slice, static_cast<hipStream_t>(stream));
+}
+
+int monta_route_dispatch_expert(const monta_cfg *cfg, const float *logits, const void *x, int32_t *topk_idx, float *gates,
+                                void *stage, void *final_, const void *w_exp, int32_t out_features, void *y, void *ws,
+                                int overlap, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if ((rc = check_route_ptrs(logits, topk_idx, gates, ws))) return rc;
+    if ((rc = check_act_ptrs(x, stage))) return rc;
+    if ((rc = check_act_ptrs(stage, final_))) return rc;
+    if (stage == final_ || y == stage || y == x) return MONTA_ERR_INVALID;
+    if ((rc = check_expert_args(cfg, g, final_, w_exp, out_features, y, ws, -1))) return rc;
+    if (overlap != 0 && overlap != 1) return MONTA_ERR_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // worst case of the rows in play: every pair of the slice's tokens kept
-    int64_t rows_bound = slice < 0 ? (int64_t)s.max_rows : std::min<int64_t>(s.max_rows, (int64_t)(s.T / s.S) * s.k);
-    ProfScope ps(MONTA_K_EXPERT, st);
-    if (cfg->dtype == MONTA_BF16) {
-        const int64_t row_tiles = (rows_bound + kExpBM - 1) / kExpBM + s.E;      // each expert may end in a ragged tile
-        const int64_t nct = (out_features + kExpBN - 1) / kExpBN;
-        const int64_t grid8 = (row_tiles * nct + kXcds - 1) / kXcds * kXcds;
-        if (grid8 > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
-        a.grid8 = (int32_t)grid8;
-        hipLaunchKernelGGL(expert_bf16_kernel, dim3((unsigned)grid8), dim3(kExpThreads), kExpLdsBytes, st,
-                           static_cast<const u32x4 *>(x_final), static_cast<const u32x4 *>(w_exp),
-                           static_cast<unsigned short *>(y), a);
-    } else {
-        a.grid8 = 0;
-        const int64_t blocks = ((int64_t)s.max_rows * out_features + 255) / 256;
-        if (blocks > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(expert_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const float *>(x_final),
-                           static_cast<const float *>(w_exp), static_cast<float *>(y), a);
+    if (!overlap) {
+        if ((rc = monta_route_dispatch_regather(cfg, logits, x, topk_idx, gates, stage, final_, ws, stream))) return rc;
+        return launch_expert_layer(cfg, g, final_, w_exp, out_features, y, ws, -1, st);
     }
-    HIP_TRY(hipGetLastError());
+    // Overlapped: the slice pipeline of pipeline mode 1 on the caller's stream, an event behind the kernel that
+    // completes a slice's rows of FINAL, and that slice's expert layer on the side stream: the matrix cores work
+    // on slice j while the movers stream slice j+1.
+    const int S = g.s.S;
+    DevState *d = nullptr;
+    if ((rc = dev_state(S, &d))) return rc;
+    if ((rc = monta_route(cfg, logits, topk_idx, gates, ws, stream))) return rc;
+    const PlanPtrs p = plan_ptrs(g, ws);
+    if ((rc = launch_pack(g, p, x, stage, 0, st))) return rc;
+    for (int j = 0; j < S; ++j) {
+        rc = j + 1 < S ? launch_pack_regather(g, p, x, stage, final_, j + 1, st)      // pack(j+1) and regather(j)
+                       : launch_regather(g, p, stage, final_, j, st);
+        if (rc) return rc;
+        HIP_TRY(hipEventRecord(d->ev[j], st));
+        HIP_TRY(hipStreamWaitEvent(d->side, d->ev[j], 0));
+        prof_break_chain(d->side);
+        if ((rc = launch_expert_layer(cfg, g, final_, w_exp, out_features, y, ws, j, d->side))) return rc;
+    }
+    HIP_TRY(hipEventRecord(d->done, d->side));
+    HIP_TRY(hipStreamWaitEvent(st, d->done, 0));
+    prof_break_chain(st);
     return MONTA_OK;
 }
 

@@ -1447,11 +1447,21 @@ __global__ __launch_bounds__(256) void gate_f32_kernel(const float4 *__restrict_
 // together on one XCD (hardware deals consecutive workgroups round robin to the 8 XCDs) are row tiles of the
 // same one or two weight tiles: the weight tile then comes from that XCD's L2 after its first reader.
 
-constexpr int kExpBM = 128, kExpBN = 256, kExpBK = 64, kExpThreads = 256;
+constexpr int kExpBK = 64, kExpThreads = 256;
 constexpr int kExpRowStride = kExpBK * 2 + 16;                                  // bytes in LDS
-constexpr int kExpLoads = (kExpBM + kExpBN) * (kExpBK / 8) / kExpThreads;       // 16-byte pieces per thread and step
-constexpr int kExpLdsBytes = (kExpBM + kExpBN) * kExpRowStride;
 constexpr int kXcds = 8;
+
+// BM x BN: the workgroup's tile of y; the 4 waves form a 2 x 2 grid, a wave owns (BM/2) x (BN/2).  One LDS buffer,
+// two barriers per step; two workgroups per CU take turns on the matrix cores.  (Measured alternatives, all slower
+// or equal on MI355X: 256 x 256 tiles with two LDS buffers and one workgroup per CU; 256 x 128; starting the
+// workgroups at different steps of the hidden axis.)
+template <int BM, int BN>
+struct ExpertTile {
+    static constexpr int kLoads = (BM + BN) / 32;                 // 16-byte pieces per thread and step
+    static constexpr int kLdsBytes = (BM + BN) * kExpRowStride;
+    static constexpr int kMT = BM / 64, kNT = BN / 64;            // MFMA tiles of a wave
+    static_assert(BM % 64 == 0 && BN % 64 == 0 && kExpBK == 64 && kExpThreads == 256, "expert kernel: tile shape");
+};
 
 struct ExpertArgs {
     const int32_t *lo;      // [E] first row of the expert's range
@@ -1467,49 +1477,52 @@ __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;       // finite inputs
 }
 
-__global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
-                                                                  unsigned short *__restrict__ y, ExpertArgs a)
+template <int BM, int BN>
+__global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4 *__restrict__ x,
+                                                                                      const u32x4 *__restrict__ w,
+                                                                                      unsigned short *__restrict__ y,
+                                                                                      ExpertArgs a)
 {
+    using G = ExpertTile<BM, BN>;
     extern __shared__ __align__(16) unsigned char exp_lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, m = lane & 31, g = lane >> 5;
     const int cpr = a.H / 8;                                       // 16-byte pieces per row in memory
-    const int nct = (a.N + kExpBN - 1) / kExpBN;                   // column tiles
+    const int nct = (a.N + BN - 1) / BN;                           // column tiles
 
     // logical tile index: each XCD gets a contiguous run; inside it (expert, column tile, row tile), row tile fastest
     int64_t L = (int64_t)(blockIdx.x % kXcds) * (a.grid8 / kXcds) + blockIdx.x / kXcds;
     int e = 0, row0 = 0, row_end = 0, ct = 0;
     for (; e < a.E; ++e) {
         const int lo = a.lo[e], hi = a.hi_base[e] + (a.hi_len ? a.hi_len[e] : 0);
-        const int tiles = hi > lo ? (hi - lo + kExpBM - 1) / kExpBM : 0;
+        const int tiles = hi > lo ? (hi - lo + BM - 1) / BM : 0;
         if (L < (int64_t)tiles * nct) {
             ct = (int)(L / tiles);
-            row0 = lo + (int)(L % tiles) * kExpBM;
+            row0 = lo + (int)(L % tiles) * BM;
             row_end = hi < a.max_rows ? hi : a.max_rows;
             break;
         }
         L -= (int64_t)tiles * nct;
     }
     if (e == a.E || row0 < 0 || row0 >= row_end) return;          // surplus workgroup (uniform for the workgroup)
-    const int col0 = ct * kExpBN;
+    const int col0 = ct * BN;
 
     // This thread's pieces of a step's tile: piece q is row tid/8 + 32*q of the tile, 16-byte column tid%8; tile rows
-    // 0..BM-1 (q < 4) are rows of x, the others rows of the weight tile.  Loads are issued unconditionally from
+    // 0..BM-1 (q < BM/32) are rows of x, the others rows of the weight tile.  Loads are issued unconditionally from
     // clamped in-bounds addresses; what lies outside becomes zeros when the tile is laid into LDS.
-    static_assert(kExpBK == 64 && kExpThreads == 256 && kExpBM == 128, "expert kernel: piece mapping assumes these");
     const u32x4 zero = {0u, 0u, 0u, 0u};
     const int r8 = tid >> 3, c_real = tid & 7;
     const int c0 = c_real < cpr ? c_real : 0;                     // rows shorter than a step: stay inside the row
-    int grow[kExpLoads];                                           // row of x, or row of w, that piece q reads
+    int grow[G::kLoads];                                           // row of x, or row of w, that piece q reads
     unsigned live = 0;
 #pragma unroll
-    for (int q = 0; q < kExpLoads; ++q) {
+    for (int q = 0; q < G::kLoads; ++q) {
         bool ok;
-        if (q < kExpBM / 32) {
+        if (q < BM / 32) {
             const int r = row0 + r8 + q * 32;
             ok = r < row_end;
             grow[q] = ok ? r : row0;
         } else {
-            const int n = col0 + r8 + (q - kExpBM / 32) * 32;
+            const int n = col0 + r8 + (q - BM / 32) * 32;
             ok = n < a.N;
             grow[q] = e * a.N + (ok ? n : 0);
         }
@@ -1518,63 +1531,66 @@ __global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4
     const int nsteps = (cpr + kExpBK / 8 - 1) / (kExpBK / 8);
     unsigned char *lay_at = exp_lds + r8 * kExpRowStride + c_real * 16;
 
-    u32x4 pre[kExpLoads];
+    u32x4 pre[G::kLoads];
     auto fetch = [&](int step) {
         const int c = step * (kExpBK / 8) + c_real < cpr ? step * (kExpBK / 8) + c0 : c0;
 #pragma unroll
-        for (int q = 0; q < kExpLoads; ++q) pre[q] = (q < kExpBM / 32 ? x : w)[(int64_t)grow[q] * cpr + c];
+        for (int q = 0; q < G::kLoads; ++q) pre[q] = (q < BM / 32 ? x : w)[(int64_t)grow[q] * cpr + c];
     };
     auto lay = [&](int step) {
         const bool col_ok = step * (kExpBK / 8) + c_real < cpr;
-        __syncthreads();                                           // the previous tile has been read by every wave
 #pragma unroll
-        for (int q = 0; q < kExpLoads; ++q)
+        for (int q = 0; q < G::kLoads; ++q)
             *reinterpret_cast<u32x4 *>(lay_at + q * 32 * kExpRowStride) = (((live >> q) & 1u) && col_ok) ? pre[q] : zero;
-        __syncthreads();
     };
 
-    f32x16 acc[2][4];
+    f32x16 acc[G::kMT][G::kNT];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < G::kMT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < G::kNT; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int wm = wave >> 1, wn = wave & 1;                       // the wave's place in the 2 x 2 grid
-    const unsigned char *pa = exp_lds + (size_t)(wm * 64 + m) * kExpRowStride + g * 16;
-    const unsigned char *pb = exp_lds + (size_t)(kExpBM + wn * 128 + m) * kExpRowStride + g * 16;
+    const unsigned char *pa = exp_lds + (size_t)(wm * (BM / 2) + m) * kExpRowStride + g * 16;
+    const unsigned char *pb = exp_lds + (size_t)(BM + wn * (BN / 2) + m) * kExpRowStride + g * 16;
+    auto multiply = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < kExpBK / 16; ++ks) {
+            bf16x8 fa[G::kMT], fb[G::kNT];
+#pragma unroll
+            for (int i = 0; i < G::kMT; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8 *>(pa + (size_t)i * 32 * kExpRowStride + ks * 32);
+#pragma unroll
+            for (int j = 0; j < G::kNT; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8 *>(pb + (size_t)j * 32 * kExpRowStride + ks * 32);
+#pragma unroll
+            for (int i = 0; i < G::kMT; ++i)
+#pragma unroll
+                for (int j = 0; j < G::kNT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    };
 
     fetch(0);
     for (int step = 0; step < nsteps; ++step) {
+        __syncthreads();                                           // the previous tile has been read by every wave
         lay(step);
+        __syncthreads();
         if (step + 1 < nsteps) fetch(step + 1);                    // in flight during the MFMAs
-#pragma unroll
-        for (int ks = 0; ks < kExpBK / 16; ++ks) {
-            bf16x8 fa[2], fb[4];
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8 *>(pa + (size_t)i * 32 * kExpRowStride + ks * 32);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8 *>(pb + (size_t)j * 32 * kExpRowStride + ks * 32);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
+        multiply();
     }
 
     // accumulator element v of a lane: row (v/4)*8 + g*4 + v%4, column m of the 32 x 32 tile
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < G::kMT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = col0 + wn * 128 + j * 32 + m;
+        for (int j = 0; j < G::kNT; ++j) {
+            const int n = col0 + wn * (BN / 2) + j * 32 + m;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int r = row0 + wm * 64 + i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+                const int r = row0 + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
                 if (r < row_end && n < a.N) y[(int64_t)r * a.N + n] = (unsigned short)f32_to_bf16_rne(acc[i][j][v]);
             }
         }

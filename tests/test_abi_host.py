@@ -124,6 +124,9 @@ def test_null_and_misaligned_pointers_fail_before_any_gpu_work():
     assert lib.monta_expert_linear(c, fake, 2 * fake, 4100, 3 * fake, fake, 0, 0) == -1      # row of y not whole vectors
     assert lib.monta_expert_linear(c, fake, 2 * fake, 4096, fake, fake, 0, 0) == -1          # in place
     assert lib.monta_expert_linear(c, fake + 4, 2 * fake, 4096, 3 * fake, fake, 0, 0) == -5
+    assert lib.monta_route_dispatch_expert(c, fake, fake, fake, fake, 2 * fake, 3 * fake, 4 * fake, 4096, 5 * fake, fake, 2, 0) == -1
+    assert lib.monta_route_dispatch_expert(c, fake, fake, fake, fake, 2 * fake, 3 * fake, 0, 4096, 5 * fake, fake, 1, 0) == -3
+    assert lib.monta_route_dispatch_expert(c, fake, fake, fake, fake, 2 * fake, 3 * fake, 4 * fake, 4096, 2 * fake, fake, 1, 0) == -1
     assert lib.monta_ws_init(c, 0, 0) == -3
     assert lib.monta_copy(0, fake, 16, 0) == -3
     assert lib.monta_copy(fake, 2 * fake, 24, 0) == -1

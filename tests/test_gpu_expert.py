@@ -182,6 +182,38 @@ def test_expert_skips_an_expert_nobody_chose(m):
     assert np.all(err <= 2.0 ** -6 * np.abs(as64(want[rows], BF16)) + 1e-6)
 
 
+@pytest.mark.parametrize("case", [CASES[0], CASES[1], CASES[3]])
+def test_overlapped_pipeline_gives_the_same_buffers(m, case):
+    """route + slice pipeline + expert layer in one call: with and without the per-slice overlap on the side stream,
+    STAGE, FINAL and y are the same as from the separate calls, run twice in a row on the same buffers."""
+    import torch
+    from paper_2411_00662_amd import buffers as bufs
+    T, H, E, k, ep, tp, S, cf, N, padded = case
+    _say(f"expert pipeline {case}")
+    w = Workload("ex", T, H, BF16, E, k, ep, tp, S, cf, padded=padded)
+    logits, x = workloads.make_inputs(w, seed=13)
+    we = workloads.make_expert_weights(w, n_out=N, seed=13)
+    cfg, b, ref = run_path(m, w, logits, x)
+    want, wd = expert_gpu(m, cfg, b, we, N)
+    R = ref.plan.R
+    L = m.monta_ws_layout_query(cfg)
+    for overlap in (0, 1, 1):
+        b2 = m.alloc_buffers(cfg, logits, x, canary=0xA5)
+        y = torch.empty((L.max_rows, N), dtype=b2.final.dtype, device="cuda:0")
+        y.view(torch.uint8).fill_(0x5A)
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            for _ in range(2):
+                m.monta_route_dispatch_expert(cfg, b2.logits, b2.x, b2.topk_idx, b2.gates, b2.stage, b2.final, wd, N, y,
+                                              b2.ws, overlap, stream)
+            m.monta_combine(cfg, b2.final, b2.gates, b2.out, b2.ws, stream)     # ordered behind the expert launches
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(b2.topk_idx.cpu().numpy(), ref.topk_idx)
+        np.testing.assert_array_equal(bufs.to_host_act(cfg, b2.stage)[:R], ref.stage[:R])
+        np.testing.assert_array_equal(bufs.to_host_act(cfg, b2.final), bufs.to_host_act(cfg, b.final))
+        np.testing.assert_array_equal(bufs.to_host_act(cfg, y), want)
+
+
 @pytest.mark.parametrize("name", ["mixtral", "2x70b"])
 def test_expert_named_workloads_full_size(m, name):
     """Full-size launch (N = H); the oracle recomputes a sample of rows, among them each segment's first and last."""
