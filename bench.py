@@ -26,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published peak
 
 
 def algorithmic_bytes(w, tabs):
@@ -71,6 +72,11 @@ def main():
     ap.add_argument("--gate", type=int, default=0,
                     help="1: the step starts one stage earlier, at the gate projection (monta_gate: logits = x * w_gate^T "
                          "with random-init weights); 0: at the logits, as the headline metric is defined")
+    ap.add_argument("--experts", type=int, default=0,
+                    help="1: a real expert layer (monta_route_dispatch_expert: one H x H linear layer per expert, random-init "
+                         "weights) sits between dispatch and combine instead of identity experts")
+    ap.add_argument("--expert-overlap", type=int, default=0,
+                    help="with --experts 1: 1 = each slice's expert launch overlaps the next slice's movers (second stream)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     args = ap.parse_args()
@@ -109,9 +115,25 @@ def main():
     w_gate_host = workloads.make_gate_weights(w) if args.gate else None
     w_gate = m.buffers.to_device_act(cfg, w_gate_host) if args.gate else None
 
+    w_exp = y_exp = None
+    if args.experts:
+        if w.dtype != workloads.BF16:
+            print("bench.py: --experts needs a bf16 workload", file=sys.stderr)
+            sys.exit(2)
+        gen = torch.Generator(device="cuda").manual_seed(20_000 + w.seed)
+        w_exp = torch.empty((w.experts, w.hidden, w.hidden), dtype=torch.bfloat16, device="cuda")
+        for e in range(w.experts):          # expert by expert: the fp32 draws of all experts at once would not fit for every workload
+            w_exp[e] = (torch.randn((w.hidden, w.hidden), generator=gen, device="cuda") / w.hidden ** 0.5).to(torch.bfloat16)
+        y_exp = torch.empty_like(b.final)
+
     def step():
         if args.gate:
             m.monta_gate(cfg, b.x, w_gate, b.logits, stream)
+        if args.experts:
+            m.monta_route_dispatch_expert(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, w_exp, w.hidden, y_exp,
+                                          b.ws, args.expert_overlap, stream)
+            m.monta_combine(cfg, y_exp, b.gates, b.out, b.ws, stream)
+            return
         m.monta_route_dispatch_regather(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, b.ws, stream)
         if mirror:
             m.monta_unregather_combine(cfg, b.final, y_stage, b.gates, b.out, b.ws, stream)
@@ -167,6 +189,10 @@ def main():
     if args.gate:
         ab["gate"] = (w.tokens + w.experts) * ab["row"] + w.tokens * w.experts * 4
         ab["total"] += ab["gate"]
+    if args.experts:
+        ab["expert_flops"] = 2.0 * ab["R"] * w.hidden * w.hidden
+        ab["expert"] = (2 * ab["R"] + w.experts * w.hidden) * ab["row"]       # rows read and written once, weights once
+        ab["total"] += ab["expert"]
     eff_gbps = ab["total"] / (ms_per_step * 1e-3) / 1e9
 
     # ---- per-kernel durations: HIP events around every launch, on the launching stream, eager launches
@@ -232,6 +258,18 @@ def main():
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                     "bytes_per_launch": int(per_launch[dom]), "avg_launch_us": round(kernels[dom]["avg_us"], 2),
                     "event_marker_us": round(marker_us, 2), "traffic": traffic}
+        if "expert" in kernels:
+            # the expert layer is a dense contraction: it is held against the matrix cores' bf16 peak
+            ek = kernels["expert"]
+            flops_per_launch = ab["expert_flops"] / max(1.0, ek["launches_per_step"])
+            tflops = flops_per_launch / (ek["avg_us"] * 1e-6) / 1e12
+            ek["TFLOPs"] = round(tflops, 1)
+            if ek["us_per_step"] > kernels[dom]["us_per_step"]:
+                roofline = {"bound": "mfma", "kernel": "expert", "achieved": round(tflops, 1),
+                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                            "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "flops_per_launch": int(flops_per_launch),
+                            "avg_launch_us": round(ek["avg_us"], 2), "event_marker_us": round(marker_us, 2),
+                            "traffic": None}
         for kname in movers:
             kernels[kname]["GBps"] = round(per_launch[kname] / (kernels[kname]["avg_us"] * 1e-6) / 1e9, 1)
         for v in kernels.values():
@@ -253,6 +291,20 @@ def main():
         import oracle
         reps, spent = 0, 0.0
         budget = 12.0
+        expert_note = ""
+        expert_s = 0.0
+        if args.experts:
+            # the expert layer on a sample of rows of one expert, scaled to all kept rows (the whole layer would take hours)
+            fwd = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm,
+                                 padded=w.padded)
+            lo, hi = oracle.expert_ranges(fwd.plan, w.tp, w.slices)
+            e0 = int(np.argmax(hi - lo))
+            n_rows = int(min(8, hi[e0] - lo[e0]))
+            w_one = workloads.make_expert_weights(w.with_(experts=1))
+            c0 = time.perf_counter()
+            oracle.expert(fwd.final[lo[e0]:lo[e0] + n_rows], w_one, np.array([0], np.int32), np.array([n_rows], np.int32))
+            expert_s = (time.perf_counter() - c0) * ab["R"] / n_rows
+            expert_note = f"; expert layer timed on {n_rows} rows and scaled to {ab['R']} ({expert_s:.0f} s per pass)"
         while reps < 20 and spent < budget:
             c0 = time.perf_counter()
             if args.gate:
@@ -261,9 +313,9 @@ def main():
                            padded=w.padded)
             spent += time.perf_counter() - c0
             reps += 1
-        cpu = {"value": round(w.tokens * reps / spent, 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
-               "sample": f"the whole {w.name} workload, {reps} passes of the single-threaded C oracle, {spent:.1f} s",
-               "effective_GBps": round(ab["total"] * reps / spent / 1e9, 2)}
+        cpu = {"value": round(w.tokens / (spent / reps + expert_s), 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+               "sample": f"the whole {w.name} workload, {reps} passes of the single-threaded C oracle, {spent:.1f} s" + expert_note,
+               "effective_GBps": round(ab["total"] / (spent / reps + expert_s) / 1e9, 2)}
 
     line = {
         "metric": "dispatch+combine tokens/s", "value": round(tokens_per_s, 1), "unit": "tokens/s",
@@ -274,7 +326,7 @@ def main():
                    "top_k": w.top_k, "ep": w.ep, "tp": w.tp, "slices": w.slices,
                    "capacity_factor": w.capacity_factor, "kept_rows": ab["R"], "alive_tokens": ab["alive"],
                    "pipeline_mode": mode, "hip_graph": use_graph, "return_path": args.return_path, "padded": w.padded,
-                   "gate": bool(args.gate),
+                   "gate": bool(args.gate), "experts": bool(args.experts), "expert_overlap": int(args.expert_overlap),
                    "parallelism": "1 GPU, virtual ep/tp"},
         "effective_GBps": round(eff_gbps, 1), "pct_of_hbm_peak": round(100 * eff_gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_bytes_per_step": int(ab["total"]),
