@@ -466,13 +466,13 @@ int launch_gate_small_any(const u32x4 *x, const u32x4 *w, float *logits, int64_t
     return 1;
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int WM, int WN>
 int launch_expert(const void *x_final, const void *w_exp, void *y, ExpertArgs a, int64_t rows_bound, hipStream_t st)
 {
-    using G = ExpertTile<BM, BN>;
+    using G = ExpertTile<BM, BN, WM, WN>;
     static std::atomic<int> lds_opt_in{0};
     if (G::kLdsBytes > 48 * 1024 && !lds_opt_in.load()) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(expert_bf16_kernel<BM, BN>),
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(expert_bf16_kernel<BM, BN, WM, WN>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, G::kLdsBytes));
         lds_opt_in.store(1);
     }
@@ -481,7 +481,7 @@ int launch_expert(const void *x_final, const void *w_exp, void *y, ExpertArgs a,
     const int64_t grid8 = (row_tiles * nct + kXcds - 1) / kXcds * kXcds;
     if (grid8 > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
     a.grid8 = (int32_t)grid8;
-    hipLaunchKernelGGL((expert_bf16_kernel<BM, BN>), dim3((unsigned)grid8), dim3(kExpThreads), G::kLdsBytes, st,
+    hipLaunchKernelGGL((expert_bf16_kernel<BM, BN, WM, WN>), dim3((unsigned)grid8), dim3(G::kThreads), G::kLdsBytes, st,
                        static_cast<const u32x4 *>(x_final), static_cast<const u32x4 *>(w_exp),
                        static_cast<unsigned short *>(y), a);
     return MONTA_OK;
@@ -557,7 +557,7 @@ int launch_expert_layer(const monta_cfg *cfg, const Geometry &g, const void *x_f
     int64_t rows_bound = slice < 0 ? (int64_t)s.max_rows : std::min<int64_t>(s.max_rows, (int64_t)(s.T / s.S) * s.k);
     ProfScope ps(MONTA_K_EXPERT, st);
     if (cfg->dtype == MONTA_BF16) {
-        rc = launch_expert<128, 256>(x_final, w_exp, y, a, rows_bound, st);
+        rc = launch_expert<128, 256, 2, 2>(x_final, w_exp, y, a, rows_bound, st);
         if (rc) return rc;
     } else {
         a.grid8 = 0;

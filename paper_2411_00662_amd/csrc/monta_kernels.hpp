@@ -1447,20 +1447,24 @@ __global__ __launch_bounds__(256) void gate_f32_kernel(const float4 *__restrict_
 // together on one XCD (hardware deals consecutive workgroups round robin to the 8 XCDs) are row tiles of the
 // same one or two weight tiles: the weight tile then comes from that XCD's L2 after its first reader.
 
-constexpr int kExpBK = 64, kExpThreads = 256;
+constexpr int kExpBK = 64;
 constexpr int kExpRowStride = kExpBK * 2 + 16;                                  // bytes in LDS
 constexpr int kXcds = 8;
 
-// BM x BN: the workgroup's tile of y; the 4 waves form a 2 x 2 grid, a wave owns (BM/2) x (BN/2).  One LDS buffer,
-// two barriers per step; two workgroups per CU take turns on the matrix cores.  (Measured alternatives, all slower
-// or equal on MI355X: 256 x 256 tiles with two LDS buffers and one workgroup per CU; 256 x 128; starting the
-// workgroups at different steps of the hidden axis.)
-template <int BM, int BN>
+// BM x BN: the workgroup's tile of y; its WM x WN waves each own (BM/WM) x (BN/WN).  One LDS buffer, two barriers
+// per step.  In use: 128 x 256 with 2 x 2 waves, two workgroups per CU.  Measured and not faster on MI355X (all
+// within 5 % of it): 256 x 256 with 8 waves, 256 x 128, two register sets of tiles in flight, two LDS buffers, and
+// staggered starts along the hidden axis; the stores of y cost nothing measurable.
+template <int BM, int BN, int WM, int WN>
 struct ExpertTile {
-    static constexpr int kLoads = (BM + BN) / 32;                 // 16-byte pieces per thread and step
+    static constexpr int kThreads = 64 * WM * WN;
+    static constexpr int kRowsPerPass = kThreads / 8;             // tile rows the threads cover with one load each
+    static constexpr int kLoads = (BM + BN) / kRowsPerPass;       // 16-byte pieces per thread and step
     static constexpr int kLdsBytes = (BM + BN) * kExpRowStride;
-    static constexpr int kMT = BM / 64, kNT = BN / 64;            // MFMA tiles of a wave
-    static_assert(BM % 64 == 0 && BN % 64 == 0 && kExpBK == 64 && kExpThreads == 256, "expert kernel: tile shape");
+    static constexpr int kMT = BM / WM / 32, kNT = BN / WN / 32;  // MFMA tiles of a wave
+    static constexpr int kWgsPerCu = kThreads <= 256 ? 2 : 1;     // what the registers allow
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && kExpBK == 64 && BM % kRowsPerPass == 0 &&
+                      BN % kRowsPerPass == 0, "expert kernel: tile shape");
 };
 
 struct ExpertArgs {
@@ -1477,13 +1481,13 @@ __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;       // finite inputs
 }
 
-template <int BM, int BN>
-__global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4 *__restrict__ x,
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN, (64 * WM * WN <= 256 ? 2 : 1)) void expert_bf16_kernel(const u32x4 *__restrict__ x,
                                                                                       const u32x4 *__restrict__ w,
                                                                                       unsigned short *__restrict__ y,
                                                                                       ExpertArgs a)
 {
-    using G = ExpertTile<BM, BN>;
+    using G = ExpertTile<BM, BN, WM, WN>;
     extern __shared__ __align__(16) unsigned char exp_lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, m = lane & 31, g = lane >> 5;
     const int cpr = a.H / 8;                                       // 16-byte pieces per row in memory
@@ -1506,8 +1510,8 @@ __global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4
     if (e == a.E || row0 < 0 || row0 >= row_end) return;          // surplus workgroup (uniform for the workgroup)
     const int col0 = ct * BN;
 
-    // This thread's pieces of a step's tile: piece q is row tid/8 + 32*q of the tile, 16-byte column tid%8; tile rows
-    // 0..BM-1 (q < BM/32) are rows of x, the others rows of the weight tile.  Loads are issued unconditionally from
+    // This thread's pieces of a step's tile: piece q is row tid/8 + (threads/8)*q of the tile, 16-byte column tid%8;
+    // tile rows 0..BM-1 are rows of x, the others rows of the weight tile.  Loads are issued unconditionally from
     // clamped in-bounds addresses; what lies outside becomes zeros when the tile is laid into LDS.
     const u32x4 zero = {0u, 0u, 0u, 0u};
     const int r8 = tid >> 3, c_real = tid & 7;
@@ -1517,12 +1521,12 @@ __global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4
 #pragma unroll
     for (int q = 0; q < G::kLoads; ++q) {
         bool ok;
-        if (q < BM / 32) {
-            const int r = row0 + r8 + q * 32;
+        if (q < BM / G::kRowsPerPass) {
+            const int r = row0 + r8 + q * G::kRowsPerPass;
             ok = r < row_end;
             grow[q] = ok ? r : row0;
         } else {
-            const int n = col0 + r8 + (q - BM / 32) * 32;
+            const int n = col0 + r8 + (q - BM / G::kRowsPerPass) * G::kRowsPerPass;
             ok = n < a.N;
             grow[q] = e * a.N + (ok ? n : 0);
         }
@@ -1531,17 +1535,20 @@ __global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4
     const int nsteps = (cpr + kExpBK / 8 - 1) / (kExpBK / 8);
     unsigned char *lay_at = exp_lds + r8 * kExpRowStride + c_real * 16;
 
-    u32x4 pre[G::kLoads];
-    auto fetch = [&](int step) {
+    // steps past the end of the hidden axis are fetched from clamped addresses and never laid down
+    auto fetch = [&](u32x4(&pre)[G::kLoads], int step) {
         const int c = step * (kExpBK / 8) + c_real < cpr ? step * (kExpBK / 8) + c0 : c0;
 #pragma unroll
-        for (int q = 0; q < G::kLoads; ++q) pre[q] = (q < BM / 32 ? x : w)[(int64_t)grow[q] * cpr + c];
+        for (int q = 0; q < G::kLoads; ++q) pre[q] = (q < BM / G::kRowsPerPass ? x : w)[(int64_t)grow[q] * cpr + c];
     };
-    auto lay = [&](int step) {
+    auto lay = [&](const u32x4(&pre)[G::kLoads], int step) {
         const bool col_ok = step * (kExpBK / 8) + c_real < cpr;
+        __syncthreads();                                           // the previous tile has been read by every wave
 #pragma unroll
         for (int q = 0; q < G::kLoads; ++q)
-            *reinterpret_cast<u32x4 *>(lay_at + q * 32 * kExpRowStride) = (((live >> q) & 1u) && col_ok) ? pre[q] : zero;
+            *reinterpret_cast<u32x4 *>(lay_at + q * G::kRowsPerPass * kExpRowStride) =
+                (((live >> q) & 1u) && col_ok) ? pre[q] : zero;
+        __syncthreads();
     };
 
     f32x16 acc[G::kMT][G::kNT];
@@ -1552,9 +1559,9 @@ __global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int wm = wave >> 1, wn = wave & 1;                       // the wave's place in the 2 x 2 grid
-    const unsigned char *pa = exp_lds + (size_t)(wm * (BM / 2) + m) * kExpRowStride + g * 16;
-    const unsigned char *pb = exp_lds + (size_t)(BM + wn * (BN / 2) + m) * kExpRowStride + g * 16;
+    const int wm = wave / WN, wn = wave % WN;                      // the wave's place in the WM x WN grid
+    const unsigned char *pa = exp_lds + (size_t)(wm * (BM / WM) + m) * kExpRowStride + g * 16;
+    const unsigned char *pb = exp_lds + (size_t)(BM + wn * (BN / WN) + m) * kExpRowStride + g * 16;
     auto multiply = [&]() {
 #pragma unroll
         for (int ks = 0; ks < kExpBK / 16; ++ks) {
@@ -1573,12 +1580,11 @@ __global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4
         }
     };
 
-    fetch(0);
+    u32x4 pre[G::kLoads];
+    fetch(pre, 0);
     for (int step = 0; step < nsteps; ++step) {
-        __syncthreads();                                           // the previous tile has been read by every wave
-        lay(step);
-        __syncthreads();
-        if (step + 1 < nsteps) fetch(step + 1);                    // in flight during the MFMAs
+        lay(pre, step);
+        fetch(pre, step + 1);                                      // in flight during the MFMAs
         multiply();
     }
 
@@ -1587,10 +1593,10 @@ __global__ __launch_bounds__(kExpThreads, 2) void expert_bf16_kernel(const u32x4
     for (int i = 0; i < G::kMT; ++i)
 #pragma unroll
         for (int j = 0; j < G::kNT; ++j) {
-            const int n = col0 + wn * (BN / 2) + j * 32 + m;
+            const int n = col0 + wn * (BN / WN) + j * 32 + m;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int r = row0 + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+                const int r = row0 + wm * (BM / WM) + i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
                 if (r < row_end && n < a.N) y[(int64_t)r * a.N + n] = (unsigned short)f32_to_bf16_rne(acc[i][j][v]);
             }
         }
