@@ -214,6 +214,64 @@ def test_overlapped_pipeline_gives_the_same_buffers(m, case):
         np.testing.assert_array_equal(bufs.to_host_act(cfg, y), want)
 
 
+@pytest.mark.parametrize("overlap", [0, 1])
+def test_gate_expert_step_in_a_hip_graph(m, overlap):
+    """gate -> route/dispatch/expert (with and without the second stream) -> combine, captured in a HIP graph and replayed
+    on changing inputs with eager work and synchronisations in between: every replay gives the eager bits."""
+    import torch
+    from paper_2411_00662_amd import buffers as bufs
+    w = Workload("ex-graph", 2048, 512, BF16, 8, 2, 4, 2, 4, 0.8)
+    cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor)
+    xs = [workloads.make_inputs(w, seed=s)[1] for s in (1, 2, 3)]
+    b = m.alloc_buffers(cfg, None, xs[0], canary=0)
+    wg = bufs.to_device_act(cfg, workloads.make_gate_weights(w, seed=1))
+    we = bufs.to_device_act(cfg, workloads.make_expert_weights(w, seed=1).reshape(-1, w.hidden))
+    y = torch.zeros_like(b.final)
+    stream = torch.cuda.Stream()
+
+    def step():
+        m.monta_gate(cfg, b.x, wg, b.logits, stream)
+        m.monta_route_dispatch_expert(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, we, w.hidden, y, b.ws,
+                                      overlap, stream)
+        m.monta_combine(cfg, y, b.gates, b.out, b.ws, stream)
+
+    def load(i):
+        b.x.copy_(torch.from_numpy(xs[i].view(np.int16)).cuda().view(torch.bfloat16))
+        torch.cuda.synchronize()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        R = m.read_tables(cfg, b.ws)["R"]
+        return R, b.topk_idx.cpu().numpy(), bufs.to_host_act(cfg, y, R).copy(), bufs.to_host_act(cfg, b.out).copy()
+
+    eager = []
+    for i in range(3):
+        load(i)
+        with torch.cuda.stream(stream):
+            step()
+        eager.append(snapshot())
+    assert not np.array_equal(eager[0][1], eager[1][1])   # the inputs really route differently
+    load(0)
+    with torch.cuda.stream(stream):
+        step()                                           # side stream and events exist before the capture
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+    for rep in range(2):
+        for i in (2, 0, 1):
+            _say(f"expert graph overlap={overlap} rep={rep} input={i}")
+            load(i)
+            b.out.zero_()
+            y.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            got = snapshot()
+            assert got[0] == eager[i][0]
+            for a_, b_ in zip(got[1:], eager[i][1:]):
+                np.testing.assert_array_equal(a_, b_)
+
+
 @pytest.mark.parametrize("name", ["mixtral", "2x70b"])
 def test_expert_named_workloads_full_size(m, name):
     """Full-size launch (N = H); the oracle recomputes a sample of rows, among them each segment's first and last."""
