@@ -466,6 +466,25 @@ int launch_gate_small_any(const u32x4 *x, const u32x4 *w, float *logits, int64_t
     return 1;
 }
 
+int launch_expert_dtl(const void *x_final, const void *w_exp, void *y, ExpertArgs a, int64_t rows_bound, hipStream_t st)
+{
+    static std::atomic<int> lds_opt_in{0};
+    if (!lds_opt_in.load()) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(expert_dtl_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kDtlLdsBytes));
+        lds_opt_in.store(1);
+    }
+    const int64_t row_tiles = (rows_bound + kDtlBM - 1) / kDtlBM + a.E;      // each expert may end in a ragged tile
+    const int64_t nct = (a.N + kDtlBN - 1) / kDtlBN;
+    const int64_t grid = row_tiles * nct;
+    if (grid > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
+    a.grid8 = 0;
+    hipLaunchKernelGGL(expert_dtl_kernel, dim3((unsigned)grid), dim3(kDtlThreads), kDtlLdsBytes, st,
+                       static_cast<const u32x4 *>(x_final), static_cast<const u32x4 *>(w_exp),
+                       static_cast<unsigned short *>(y), a);
+    return MONTA_OK;
+}
+
 template <int BM, int BN, int WM, int WN>
 int launch_expert(const void *x_final, const void *w_exp, void *y, ExpertArgs a, int64_t rows_bound, hipStream_t st)
 {
@@ -557,7 +576,11 @@ int launch_expert_layer(const monta_cfg *cfg, const Geometry &g, const void *x_f
     int64_t rows_bound = slice < 0 ? (int64_t)s.max_rows : std::min<int64_t>(s.max_rows, (int64_t)(s.T / s.S) * s.k);
     ProfScope ps(MONTA_K_EXPERT, st);
     if (cfg->dtype == MONTA_BF16) {
-        rc = launch_expert<128, 256, 2, 2>(x_final, w_exp, y, a, rows_bound, st);
+        // whole 64-element steps and segments long enough for 256-row tiles: the direct-to-LDS kernel
+        if (cfg->hidden % 64 == 0 && rows_bound / s.E >= 256)
+            rc = launch_expert_dtl(x_final, w_exp, y, a, rows_bound, st);
+        else
+            rc = launch_expert<128, 256, 2, 2>(x_final, w_exp, y, a, rows_bound, st);
         if (rc) return rc;
     } else {
         a.grid8 = 0;

@@ -1602,6 +1602,126 @@ __global__ __launch_bounds__(64 * WM * WN, (64 * WM * WN <= 256 ? 2 : 1)) void e
         }
 }
 
+// The same contraction with direct-to-LDS loads (global_load_lds_dwordx4: 64 lanes x 16 bytes land in 1 KiB of
+// LDS that the instruction addresses, lane i at byte 16*i, without passing through registers).  That frees the
+// registers the staged tile occupied, so 8 waves can hold a 256 x 256 tile of y (a wave 128 x 64), which halves
+// the L2 traffic per flop, and a step needs one barrier instead of two: the next step's tile streams into the other
+// of two LDS buffers while the MFMAs run.  Rows are 128 bytes in LDS without padding; the 16-byte piece c of row r
+// sits at position c ^ (r % 8), which keeps the fragment reads conflict-free; since the LDS position of a lane's
+// data is fixed by the instruction, the swizzle is applied on the global side (lane i of a chunk of 8 rows fetches
+// piece (i % 8) ^ (i / 8) of row i / 8).  Needs H to be a multiple of 64 (a tail step cannot be zero-filled on
+// this path); rows past a segment's end are fetched from its last row and their results are not stored.
+// Measured on MI355X (16384 x 4096 x 4096, one expert): 590-610 us against 715-740 us for the register-staged
+// kernel.  A segment's ragged last tile costs a full tile's time (the steps are bound by their loads, so skipping the
+// MFMAs of its empty 32-row blocks was measured and does not pay).
+constexpr int kDtlBM = 256, kDtlBN = 256, kDtlWM = 2, kDtlWN = 4, kDtlThreads = 64 * kDtlWM * kDtlWN;
+constexpr int kDtlStageBytes = (kDtlBM + kDtlBN) * 128;
+constexpr int kDtlLdsBytes = 2 * kDtlStageBytes;
+
+__global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
+                                                                 unsigned short *__restrict__ y, ExpertArgs a)
+{
+    constexpr int BM = kDtlBM, BN = kDtlBN, WM = kDtlWM, WN = kDtlWN, WAVES = WM * WN;
+    constexpr int CPW = (BM + BN) / 8 / WAVES;                     // 1 KiB chunks (8 tile rows) per wave and step
+    constexpr int MT = BM / WM / 32, NT = BN / WN / 32;
+    static_assert((BM + BN) % (8 * WAVES) == 0 && BM % 8 == 0, "expert_dtl_kernel: chunks must divide among the waves");
+    extern __shared__ __align__(16) unsigned char dtl_lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, m = lane & 31, g = lane >> 5;
+    const int cpr = a.H / 8, nsteps = a.H / 64;
+    const int nct = (a.N + BN - 1) / BN;
+
+    // tile of this workgroup: (expert, column tile, row tile), row tile fastest; consecutive workgroups go to
+    // different XCDs and share the weight tile through the memory-side cache (numbering them so that an XCD keeps
+    // a weight tile to itself measured slower)
+    int64_t L = blockIdx.x;
+    int e = 0, row0 = 0, row_end = 0, ct = 0;
+    for (; e < a.E; ++e) {
+        const int lo = a.lo[e], hi = a.hi_base[e] + (a.hi_len ? a.hi_len[e] : 0);
+        const int tiles = hi > lo ? (hi - lo + BM - 1) / BM : 0;
+        if (L < (int64_t)tiles * nct) {
+            ct = (int)(L / tiles);
+            row0 = lo + (int)(L % tiles) * BM;
+            row_end = hi < a.max_rows ? hi : a.max_rows;
+            break;
+        }
+        L -= (int64_t)tiles * nct;
+    }
+    if (e == a.E || row0 < 0 || row0 >= row_end) return;          // surplus workgroup (uniform for the workgroup)
+    const int col0 = ct * BN;
+
+    // source of this lane in each of its wave's chunks: row (chunk*8 + lane/8) of the tile, piece (lane%8)^(lane/8)
+    const int lr = lane >> 3, lc = (lane & 7) ^ lr;
+    const u32x4 *src[CPW];
+#pragma unroll
+    for (int q = 0; q < CPW; ++q) {
+        const int trow = (wave * CPW + q) * 8 + lr;
+        if (trow < BM) {
+            const int r = row0 + trow;
+            src[q] = x + (int64_t)(r < row_end ? r : row_end - 1) * cpr + lc;
+        } else {
+            const int n = col0 + trow - BM;
+            src[q] = w + ((int64_t)e * a.N + (n < a.N ? n : a.N - 1)) * cpr + lc;
+        }
+    }
+    auto issue = [&](int step, int buf) {
+#pragma unroll
+        for (int q = 0; q < CPW; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1))) *)(src[q] + step * 8),
+                (void __attribute__((address_space(3))) *)(dtl_lds + buf * kDtlStageBytes + (wave * CPW + q) * 1024), 16, 0, 0);
+    };
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int wm = wave / WN, wn = wave % WN;
+    const unsigned char *pa = dtl_lds + (size_t)(wm * (BM / WM) + m) * 128;
+    const unsigned char *pb = dtl_lds + (size_t)(BM + wn * (BN / WN) + m) * 128;
+    int koff[kExpBK / 16];                                         // byte offset of this lane's fragment piece per k-slice
+#pragma unroll
+    for (int ks = 0; ks < kExpBK / 16; ++ks) koff[ks] = ((2 * ks + g) ^ (m & 7)) * 16;
+
+    issue(0, 0);
+    for (int step = 0; step < nsteps; ++step) {
+        // s_waitcnt vmcnt(0) (expcnt and lgkmcnt left at their maxima): this step's tile has landed in LDS
+        __builtin_amdgcn_s_waitcnt(0x0f70);
+        __syncthreads();                                           // ... for every wave, and the other buffer is free
+        if (step + 1 < nsteps) issue(step + 1, (step + 1) & 1);    // streams in during the MFMAs
+        const int buf = (step & 1) * kDtlStageBytes;
+#pragma unroll
+        for (int ks = 0; ks < kExpBK / 16; ++ks) {
+            bf16x8 fa[MT], fb[NT];
+#pragma unroll
+            for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const bf16x8 *>(pa + buf + i * 32 * 128 + koff[ks]);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) fb[j] = *reinterpret_cast<const bf16x8 *>(pb + buf + j * 32 * 128 + koff[ks]);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // accumulator element v of a lane: row (v/4)*8 + g*4 + v%4, column m of the 32 x 32 tile
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int n = col0 + wn * (BN / WN) + j * 32 + m;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = row0 + wm * (BM / WM) + i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+                if (r < row_end && n < a.N) y[(int64_t)r * a.N + n] = (unsigned short)f32_to_bf16_rne(acc[i][j][v]);
+            }
+        }
+}
+
 // fp32 activations (small test shapes only): one thread per output element, fp32 fused multiply-adds
 __global__ __launch_bounds__(256) void expert_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                          float *__restrict__ y, ExpertArgs a)

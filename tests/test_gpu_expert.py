@@ -88,6 +88,10 @@ CASES = [
     (256, 24, 8, 1, 2, 2, 2, 0.0, 40, 0),
     (640, 136, 5, 3, 1, 2, 2, 0.5, 256, 1),
     (2048, 256, 2, 1, 2, 4, 2, 0.0, 8, 0),
+    # long segments and whole 64-element steps: the direct-to-LDS kernel (256-row tiles), ragged segment ends, drops,
+    # a ragged second column tile, the padded layout
+    (4096, 128, 3, 2, 3, 2, 2, 0.9, 264, 0),
+    (3072, 192, 2, 2, 1, 1, 3, 0.7, 512, 1),
 ]
 
 
@@ -123,7 +127,7 @@ def test_expert_small_integers_bit_exact(m, case, dtype):
 
 
 @pytest.mark.parametrize("dtype", [BF16, FP32])
-@pytest.mark.parametrize("case", CASES[:4])
+@pytest.mark.parametrize("case", CASES[:4] + CASES[5:])
 def test_expert_normal_inputs_within_bound(m, case, dtype):
     T, H, E, k, ep, tp, S, cf, N, padded = case
     _say(f"expert normal {case} dtype={dtype}")
@@ -182,7 +186,7 @@ def test_expert_skips_an_expert_nobody_chose(m):
     assert np.all(err <= 2.0 ** -6 * np.abs(as64(want[rows], BF16)) + 1e-6)
 
 
-@pytest.mark.parametrize("case", [CASES[0], CASES[1], CASES[3]])
+@pytest.mark.parametrize("case", [CASES[0], CASES[1], CASES[3], CASES[5], CASES[6]])
 def test_overlapped_pipeline_gives_the_same_buffers(m, case):
     """route + slice pipeline + expert layer in one call: with and without the per-slice overlap on the side stream,
     STAGE, FINAL and y are the same as from the separate calls, run twice in a row on the same buffers."""
