@@ -152,6 +152,40 @@ def test_expert_normal_inputs_within_bound(m, case, dtype):
     np.testing.assert_array_equal(again, got)
 
 
+def test_expert_random_shapes_bit_exact(m):
+    """Seeded random shapes on both kernels (long segments with whole 64-element steps, and everything else), small
+    integers so that the comparison is exact; whole buffer and slice by slice."""
+    rng = np.random.default_rng(2024)
+    for it in range(12):
+        E = int(rng.choice([1, 2, 3, 4, 6, 8]))
+        k = int(rng.integers(1, min(E, 3) + 1))
+        tp = int(rng.choice([1, 2, 4]))
+        S = int(rng.choice([1, 2, 3, 4]))
+        long_segments = it % 2 == 0
+        T = S * tp * int(rng.integers(40, 90) if not long_segments else rng.integers(150, 400) * max(1, E // 2))
+        H = int(rng.choice([64, 128, 192, 320]) if long_segments else rng.choice([8, 24, 72, 200, 256]))
+        N = int(rng.choice([8, 64, 136, 256, 264, 520]))
+        cf = float(rng.choice([0.0, 0.6, 1.1]))
+        padded = int(rng.integers(0, 2))
+        ep = int(rng.choice([d for d in (1, 2, 3, 4) if E % d == 0]))
+        case = (T, H, E, k, ep, tp, S, cf, N, padded)
+        _say(f"expert random {it}: {case}")
+        w = Workload("exr", T, H, BF16, E, k, ep, tp, S, cf, padded=padded)
+        logits = workloads.make_logits(w, seed=100 + it)
+        x = to_act(rng.integers(-4, 5, size=(T, H)).astype(np.float32), BF16)
+        we = to_act(rng.integers(-4, 5, size=(E, N, H)).astype(np.float32), BF16)
+        cfg, b, ref = run_path(m, w, logits, x)
+        pl = ref.plan
+        lo, hi = oracle.expert_ranges(pl, tp, S)
+        want = oracle.expert(ref.final, we, lo, hi)
+        got, _ = expert_gpu(m, cfg, b, we, N)
+        rows = check_untouched(got, pl)
+        np.testing.assert_array_equal(got[rows], want[rows], err_msg=str(case))
+        got2, _ = expert_gpu(m, cfg, b, we, N, slices=tuple(range(S)))
+        check_untouched(got2, pl)
+        np.testing.assert_array_equal(got2[rows], want[rows], err_msg=str(case))
+
+
 def test_expert_identity_weights_reproduce_the_identity_expert_path(m):
     """w[e] = I: y equals FINAL on the kept rows, and combine of y equals combine of FINAL."""
     import torch
