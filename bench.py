@@ -326,7 +326,7 @@ def main():
                    "top_k": w.top_k, "ep": w.ep, "tp": w.tp, "slices": w.slices,
                    "capacity_factor": w.capacity_factor, "kept_rows": ab["R"], "alive_tokens": ab["alive"],
                    "pipeline_mode": mode, "hip_graph": use_graph, "return_path": args.return_path, "padded": w.padded,
-                   "gate": bool(args.gate), "experts": bool(args.experts), "expert_overlap": int(args.expert_overlap),
+                   "gate": bool(args.gate), "expert_layer": bool(args.experts), "expert_overlap": int(args.expert_overlap),
                    "parallelism": "1 GPU, virtual ep/tp"},
         "effective_GBps": round(eff_gbps, 1), "pct_of_hbm_peak": round(100 * eff_gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_bytes_per_step": int(ab["total"]),
