@@ -1237,8 +1237,8 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const u32x4 *__
 // holds w[e][quarter qk'], so the diagonal blocks qk = qk' of the accumulator carry the four quarter sums of
 // every (token, expert) logit, and the off-diagonal blocks, which would be idle columns anyway with so few
 // experts, are ignored.  The weights never change, so a persistent workgroup keeps its B fragments in registers
-// for the whole launch: wave v owns steps v, v+8, ... of each quarter.  Sums over quarters (two lane shuffles),
-// over waves (LDS, fixed order) and over chunks (the accumulator) are in a fixed order: results are reproducible.
+// for the whole launch: wave v owns steps v, v+8, ... of each quarter.  The sums over chunks (in the accumulator) and
+// over waves and quarters (through LDS, by 64 threads, one tile later) run in a fixed order: results are reproducible.
 
 constexpr int kGateSmallTokens = 8;          // rows of one tile
 constexpr int kGateSmallExperts = 8;         // expert slots of one quarter
