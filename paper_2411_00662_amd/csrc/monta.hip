@@ -476,7 +476,8 @@ int launch_expert_dtl(const void *x_final, const void *w_exp, void *y, ExpertArg
     }
     const int64_t row_tiles = (rows_bound + kDtlBM - 1) / kDtlBM + a.E;      // each expert may end in a ragged tile
     const int64_t nct = (a.N + kDtlBN - 1) / kDtlBN;
-    const int64_t grid = row_tiles * nct;
+    // whole blocks of 256 workgroups: the kernel hands out tile numbers in such blocks, 32 per XCD
+    const int64_t grid = (row_tiles * nct + 32 * kXcds - 1) / (32 * kXcds) * (32 * kXcds);
     if (grid > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
     a.grid8 = 0;
     hipLaunchKernelGGL(expert_dtl_kernel, dim3((unsigned)grid), dim3(kDtlThreads), kDtlLdsBytes, st,

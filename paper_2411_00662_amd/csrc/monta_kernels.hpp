@@ -1630,17 +1630,31 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
     const int cpr = a.H / 8, nsteps = a.H / 64;
     const int nct = (a.N + BN - 1) / BN;
 
-    // tile of this workgroup: (expert, column tile, row tile), row tile fastest; consecutive workgroups go to
-    // different XCDs and share the weight tile through the memory-side cache (numbering them so that an XCD keeps
-    // a weight tile to itself measured slower)
-    int64_t L = blockIdx.x;
+    // Tile of this workgroup.  Hardware deals consecutive workgroups round robin to the 8 XCDs, each with its own L2;
+    // the 32 workgroups that run together on one XCD should share tiles of x and of the weights.  So logical tile
+    // numbers are handed out in blocks of 256, XCD i taking numbers 32 i .. 32 i + 31 of each block, and inside an
+    // expert the numbering is (panel of 8 row tiles, column tile, row tile in the panel), innermost fastest: an XCD
+    // then works on 8 row tiles x 4 column tiles at a time (12 distinct operand tiles instead of 33).
+    const int64_t j = blockIdx.x / kXcds;
+    int64_t L = (j / 32) * (32 * kXcds) + (int64_t)(blockIdx.x % kXcds) * 32 + j % 32;
     int e = 0, row0 = 0, row_end = 0, ct = 0;
     for (; e < a.E; ++e) {
         const int lo = a.lo[e], hi = a.hi_base[e] + (a.hi_len ? a.hi_len[e] : 0);
         const int tiles = hi > lo ? (hi - lo + BM - 1) / BM : 0;
         if (L < (int64_t)tiles * nct) {
-            ct = (int)(L / tiles);
-            row0 = lo + (int)(L % tiles) * BM;
+            constexpr int P = 8;                                   // row tiles of a panel (4..32 measure alike)
+            const int full = tiles / P;                            // whole panels
+            int rt;
+            if (L < (int64_t)full * P * nct) {
+                const int p = (int)(L / (P * nct)), rem = (int)(L % (P * nct));
+                ct = rem / P;
+                rt = p * P + rem % P;
+            } else {
+                const int rem = (int)(L - (int64_t)full * P * nct), pr = tiles - full * P;
+                ct = rem / pr;
+                rt = full * P + rem % pr;
+            }
+            row0 = lo + rt * BM;
             row_end = hi < a.max_rows ? hi : a.max_rows;
             break;
         }
