@@ -498,9 +498,10 @@ int launch_expert(const void *x_final, const void *w_exp, void *y, ExpertArgs a,
     }
     const int64_t row_tiles = (rows_bound + BM - 1) / BM + a.E;      // each expert may end in a ragged tile
     const int64_t nct = (a.N + BN - 1) / BN;
-    const int64_t grid8 = (row_tiles * nct + kXcds - 1) / kXcds * kXcds;
+    constexpr int64_t block = 32 * G::kWgsPerCu * kXcds;            // the kernel numbers its tiles in such blocks
+    const int64_t grid8 = (row_tiles * nct + block - 1) / block * block;
     if (grid8 > 0x7fffffff) return MONTA_ERR_UNSUPPORTED;
-    a.grid8 = (int32_t)grid8;
+    a.grid8 = 0;
     hipLaunchKernelGGL((expert_bf16_kernel<BM, BN, WM, WN>), dim3((unsigned)grid8), dim3(G::kThreads), G::kLdsBytes, st,
                        static_cast<const u32x4 *>(x_final), static_cast<const u32x4 *>(w_exp),
                        static_cast<unsigned short *>(y), a);

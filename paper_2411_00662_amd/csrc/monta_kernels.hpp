@@ -1443,9 +1443,9 @@ __global__ __launch_bounds__(256) void gate_f32_kernel(const float4 *__restrict_
 // bf16: a workgroup of 4 waves computes a 128 x 256 tile of y (rows x output features) of one expert; the hidden
 // axis goes in steps of 64 elements through registers into LDS (rows padded by 16 bytes, as in the gate kernels).
 // The waves form a 2 x 2 grid; a wave owns 64 x 128 = 2 x 4 MFMA tiles (128 accumulator registers), so every A
-// fragment read from LDS feeds 4 MFMAs and every B fragment 2.  Workgroups are numbered so that the 32 which run
+// fragment read from LDS feeds 4 MFMAs and every B fragment 2.  Workgroups are numbered so that those which run
 // together on one XCD (hardware deals consecutive workgroups round robin to the 8 XCDs) are row tiles of the
-// same one or two weight tiles: the weight tile then comes from that XCD's L2 after its first reader.
+// same few weight tiles: the weight tile then comes from that XCD's L2 after its first reader.
 
 constexpr int kExpBK = 64;
 constexpr int kExpRowStride = kExpBK * 2 + 16;                                  // bytes in LDS
@@ -1472,7 +1472,7 @@ struct ExpertArgs {
     const int32_t *hi_base; // [E] one past its last row is hi_base[e] + hi_len[e] ...
     const int32_t *hi_len;  // [E] ... or hi_base[e] alone if this is nullptr
     int32_t E, H, N, max_rows;
-    int32_t grid8;          // launched workgroups, a multiple of kXcds
+    int32_t grid8;          // unused
 };
 
 __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f)
@@ -1493,8 +1493,12 @@ __global__ __launch_bounds__(64 * WM * WN, (64 * WM * WN <= 256 ? 2 : 1)) void e
     const int cpr = a.H / 8;                                       // 16-byte pieces per row in memory
     const int nct = (a.N + BN - 1) / BN;                           // column tiles
 
-    // logical tile index: each XCD gets a contiguous run; inside it (expert, column tile, row tile), row tile fastest
-    int64_t L = (int64_t)(blockIdx.x % kXcds) * (a.grid8 / kXcds) + blockIdx.x / kXcds;
+    // logical tile numbers go out in blocks, XCD i taking kPerXcd consecutive numbers of each block (the workgroups
+    // that run together on one XCD, which hardware fills round robin, then share operand tiles, and surplus numbers at
+    // the end are spread over all XCDs); the numbering is (expert, column tile, row tile), row tile fastest
+    constexpr int kPerXcd = 32 * G::kWgsPerCu;
+    const int64_t jx = blockIdx.x / kXcds;
+    int64_t L = (jx / kPerXcd) * (kPerXcd * kXcds) + (int64_t)(blockIdx.x % kXcds) * kPerXcd + jx % kPerXcd;
     int e = 0, row0 = 0, row_end = 0, ct = 0;
     for (; e < a.E; ++e) {
         const int lo = a.lo[e], hi = a.hi_base[e] + (a.hi_len ? a.hi_len[e] : 0);
