@@ -1239,6 +1239,8 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const u32x4 *__
 // experts, are ignored.  The weights never change, so a persistent workgroup keeps its B fragments in registers
 // for the whole launch: wave v owns steps v, v+8, ... of each quarter.  The sums over chunks (in the accumulator) and
 // over waves and quarters (through LDS, by 64 threads, one tile later) run in a fixed order: results are reproducible.
+// (A variant with direct-to-LDS loads, three tile buffers and two tiles in flight measured the same within 3 % on
+// MI355X and is not kept.)
 
 constexpr int kGateSmallTokens = 8;          // rows of one tile
 constexpr int kGateSmallExperts = 8;         // expert slots of one quarter

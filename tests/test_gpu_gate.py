@@ -66,6 +66,9 @@ SHAPES = [(1, 8, 1), (31, 64, 7), (100, 200, 8), (257, 1032, 33), (64, 4096, 64)
           # at most 8 experts and whole 64-element quarters: the persistent whole-row kernel, one and two chunks per row,
           # quarters that are not powers of two, fewer MFMA steps than waves, more groups than workgroups
           (70, 8192, 8), (45, 7168, 3), (19, 1088, 5), (300, 2048, 2), (64, 128, 8), (9, 4160, 1), (5000, 256, 6),
+          # whole chunks of 512 / 1024 / 2048 elements: the direct-to-LDS form (one to seven chunks a row, ragged last group,
+          # more groups than workgroups)
+          (50, 1024, 3), (77, 512, 8), (130, 1536, 5), (3000, 2048, 8), (9, 6144, 2), (300, 5120, 7), (4100, 512, 4),
           # many tokens and more than 32 experts: 128-token workgroups, a wave per output tile (one, two and four
           # tiles per wave), ragged last workgroup, hidden sizes that are not whole steps
           (32773, 64, 64), (32800, 72, 100), (32769, 136, 200), (33000, 200, 33)]
