@@ -410,17 +410,31 @@ int check_act_ptrs(const void *a, const void *b)
     return MONTA_OK;
 }
 
+// Dynamic LDS above the default limit has to be asked for once per kernel and device.
+struct LdsOptIn {
+    std::atomic<int> done[64];
+};
+
+int opt_in_lds(const void *kernel, int bytes, LdsOptIn &state)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return MONTA_ERR_UNSUPPORTED;
+    if (!state.done[dev].load()) {
+        HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+        state.done[dev].store(1);
+    }
+    return MONTA_OK;
+}
+
 template <int MT, int NT, int KS, bool DEEP, bool SPLIT = false>
 int launch_gate(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, int H, int E, hipStream_t st)
 {
     using G = GateTile<MT, NT, KS>;
-    static std::atomic<int> lds_opt_in{0};
-    if (!lds_opt_in.load()) {
-        // dynamic LDS above the default limit has to be asked for once per kernel
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gate_bf16_kernel<MT, NT, KS, DEEP, SPLIT>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::lds_bytes(32 * NT, !SPLIT)));
-        lds_opt_in.store(1);
-    }
+    static LdsOptIn lds_opt_in;
+    if (int rc = opt_in_lds(reinterpret_cast<const void *>(gate_bf16_kernel<MT, NT, KS, DEEP, SPLIT>),
+                            (int)G::lds_bytes(32 * NT, !SPLIT), lds_opt_in))
+        return rc;
     const unsigned grid = (unsigned)((T + G::kTokens - 1) / G::kTokens);
     hipLaunchKernelGGL((gate_bf16_kernel<MT, NT, KS, DEEP, SPLIT>), dim3(grid), dim3(kGateThreads), G::lds_bytes(E, !SPLIT), st, x, w, logits,
                        T, H, E);
@@ -431,13 +445,10 @@ template <int NCH, int THREADS, int MAXCHUNK>
 int launch_gate_small(const u32x4 *x, const u32x4 *w, float *logits, int64_t T, int H, int E, int wgs_per_cu,
                       hipStream_t st)
 {
-    static std::atomic<int> lds_opt_in{0};
-    if (!lds_opt_in.load()) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gate_small_kernel<NCH, THREADS, MAXCHUNK>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)gate_small_lds_bytes(MAXCHUNK, THREADS)));
-        lds_opt_in.store(1);
-    }
+    static LdsOptIn lds_opt_in;
+    if (int rc = opt_in_lds(reinterpret_cast<const void *>(gate_small_kernel<NCH, THREADS, MAXCHUNK>),
+                            (int)gate_small_lds_bytes(MAXCHUNK, THREADS), lds_opt_in))
+        return rc;
     static std::atomic<int> cus{0};
     if (!cus.load()) {
         int dev = 0, n = 0;
@@ -468,12 +479,8 @@ int launch_gate_small_any(const u32x4 *x, const u32x4 *w, float *logits, int64_t
 
 int launch_expert_dtl(const void *x_final, const void *w_exp, void *y, ExpertArgs a, int64_t rows_bound, hipStream_t st)
 {
-    static std::atomic<int> lds_opt_in{0};
-    if (!lds_opt_in.load()) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(expert_dtl_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kDtlLdsBytes));
-        lds_opt_in.store(1);
-    }
+    static LdsOptIn lds_opt_in;
+    if (int rc = opt_in_lds(reinterpret_cast<const void *>(expert_dtl_kernel), kDtlLdsBytes, lds_opt_in)) return rc;
     const int64_t row_tiles = (rows_bound + kDtlBM - 1) / kDtlBM + a.E;      // each expert may end in a ragged tile
     const int64_t nct = (a.N + kDtlBN - 1) / kDtlBN;
     // whole blocks of 256 workgroups: the kernel hands out tile numbers in such blocks, 32 per XCD
@@ -490,12 +497,9 @@ template <int BM, int BN, int WM, int WN>
 int launch_expert(const void *x_final, const void *w_exp, void *y, ExpertArgs a, int64_t rows_bound, hipStream_t st)
 {
     using G = ExpertTile<BM, BN, WM, WN>;
-    static std::atomic<int> lds_opt_in{0};
-    if (G::kLdsBytes > 48 * 1024 && !lds_opt_in.load()) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(expert_bf16_kernel<BM, BN, WM, WN>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, G::kLdsBytes));
-        lds_opt_in.store(1);
-    }
+    static LdsOptIn lds_opt_in;
+    if (int rc = opt_in_lds(reinterpret_cast<const void *>(expert_bf16_kernel<BM, BN, WM, WN>), G::kLdsBytes, lds_opt_in))
+        return rc;
     const int64_t row_tiles = (rows_bound + BM - 1) / BM + a.E;      // each expert may end in a ragged tile
     const int64_t nct = (a.N + BN - 1) / BN;
     constexpr int64_t block = 32 * G::kWgsPerCu * kXcds;            // the kernel numbers its tiles in such blocks
@@ -511,13 +515,9 @@ int launch_expert(const void *x_final, const void *w_exp, void *y, ExpertArgs a,
 int launch_route(const Geometry &g, const PlanPtrs &p, const float *logits, int32_t *topk_idx, float *gates,
                  hipStream_t st)
 {
-    static std::atomic<int> lds_opt_in{0};
-    if (g.route_lds > 48 * 1024 && !lds_opt_in.load()) {
-        // dynamic LDS above the default limit has to be asked for once per kernel
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(route_plan_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRouteLdsBudget));
-        lds_opt_in.store(1);
-    }
+    static LdsOptIn lds_opt_in;
+    if (g.route_lds > 48 * 1024)
+        if (int rc = opt_in_lds(reinterpret_cast<const void *>(route_plan_kernel), (int)kRouteLdsBudget, lds_opt_in)) return rc;
     ProfScope ps(MONTA_K_ROUTE, st);
     hipLaunchKernelGGL(route_plan_kernel, dim3(g.s.num_blocks), dim3(g.route_threads), g.route_lds, st, logits,
                        topk_idx, gates, p, g.s);
