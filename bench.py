@@ -305,7 +305,7 @@ def main():
             oracle.expert(fwd.final[lo[e0]:lo[e0] + n_rows], w_one, np.array([0], np.int32), np.array([n_rows], np.int32))
             expert_s = (time.perf_counter() - c0) * ab["R"] / n_rows
             expert_note = f"; expert layer timed on {n_rows} rows and scaled to {ab['R']} ({expert_s:.0f} s per pass)"
-        while reps < 20 and spent < budget:
+        while reps < 200 and spent < budget:
             c0 = time.perf_counter()
             if args.gate:
                 logits = oracle.gate(x, w_gate_host)

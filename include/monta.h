@@ -26,6 +26,13 @@
  *   - Return value: MONTA_OK (0) or a negative monta_status.  Arguments are
  *     validated before the first HIP call, so bad arguments never reach the GPU.
  *     Nothing throws or aborts across this boundary.
+ *   - Threads.  Entry points may be called from several host threads as long as
+ *     calls that share a workspace or a buffer are ordered by the caller (same
+ *     stream, or events).  The forms that use the library's side stream
+ *     (pipeline mode 0, monta_route_dispatch_expert with overlap = 1) share one
+ *     side stream and one set of events per device: two such calls in flight on
+ *     one device must come from one thread at a time.  The monta_set_* switches
+ *     are process-wide.
  *   - Limits: 1 <= top_k <= experts <= 256, top_k <= 32, experts % ep == 0,
  *     tokens % (slices * tp) == 0, tokens * top_k < 2^31,
  *     hidden * sizeof(element) % 16 == 0; activation base pointers 16-byte

@@ -16,13 +16,12 @@
 #include "monta_kernels.hpp"
 #include "monta_planner.hpp"
 
-#ifndef MONTA_COMBINE_WIDE_VPR
-#define MONTA_COMBINE_WIDE_VPR (2 * kMoverThreads)
-#endif
-
 namespace {
 
 using namespace monta;
+
+// rows above this many 16-byte vectors (8 KiB) are combined with 4 vectors per lane and pass instead of 2
+constexpr int kCombineWideVpr = 2 * kMoverThreads;
 
 thread_local int g_last_hip = 0;
 std::atomic<int> g_pipeline_mode{1};
@@ -106,11 +105,7 @@ int validate(const monta_cfg *c, Geometry *g)
     s.C = (int32_t)capacity_of(c);
     s.renorm = c->renorm;
     s.vpr = (int32_t)(row / 16);
-#ifdef MONTA_LPR_MAX
-    const int lpr_max = MONTA_LPR_MAX;
-#else
     const int lpr_max = kMoverThreads;
-#endif
     s.lpr = pow2ceil(s.vpr) < lpr_max ? pow2ceil(s.vpr) : lpr_max;
     // route workgroup: as many tokens as fit the LDS budget (gfx950 gives a workgroup up to 160 KiB),
     // at most 256, no more than a unit needs
@@ -539,8 +534,6 @@ int check_route_ptrs(const float *logits, const int32_t *topk_idx, const float *
     return check_ws(ws);
 }
 
-}  // namespace
-
 int check_expert_args(const monta_cfg *cfg, const Geometry &g, const void *x_final, const void *w_exp, int32_t out_features,
                       const void *y, const void *ws, int slice)
 {
@@ -594,6 +587,8 @@ int launch_expert_layer(const monta_cfg *cfg, const Geometry &g, const void *x_f
     HIP_TRY(hipGetLastError());
     return MONTA_OK;
 }
+
+}  // namespace
 
 extern "C" {
 
@@ -868,7 +863,7 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
     hipStream_t st = static_cast<hipStream_t>(stream);
     ProfScope ps(MONTA_K_COMBINE, st);
     const dim3 grid(mover_grid(s, s.T)), block(kMoverThreads);
-    const bool wide = s.vpr > MONTA_COMBINE_WIDE_VPR;   // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
+    const bool wide = s.vpr > kCombineWideVpr;   // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
     const u32x4 *yv = static_cast<const u32x4 *>(y);
     u32x4 *ov = static_cast<u32x4 *>(out);
     if (cfg->dtype == MONTA_BF16) {
@@ -943,7 +938,7 @@ int launch_unregather_combine(const Geometry &g, const PlanPtrs &p, int dtype, c
     const int n_unreg = u0 < u1 ? regather_grid(s, slice_rows_bound(g, (u1 - u0) / s.tp)) : 0;
     const int n_comb = nt > 0 ? mover_grid(s, nt) : 0;
     if (n_unreg + n_comb == 0) return MONTA_OK;
-    const bool wide = s.vpr > MONTA_COMBINE_WIDE_VPR;
+    const bool wide = s.vpr > kCombineWideVpr;
     const u32x4 *yv = static_cast<const u32x4 *>(y);
     u32x4 *sv = static_cast<u32x4 *>(y_stage), *ov = static_cast<u32x4 *>(out);
     const dim3 grid(n_unreg + n_comb), block(kMoverThreads);

@@ -1,14 +1,17 @@
 // Device code of the MoE dispatch / combine path for gfx950 (wave64).
 //
-// Everything here is bandwidth or latency bound; there is no dense contraction
-// on the path, so no MFMA.  The row movers (pack, regather, combine) move rows of
-// 16-byte vectors straight through registers with several loads in flight per
-// lane; the planning kernels are integer work on wavefront bit masks.
+// The path itself (route, plan, pack, regather, combine and the mirrored return path)
+// is bandwidth or latency bound: no dense contraction, so no MFMA.  The row movers
+// move rows of 16-byte vectors straight through registers with several loads in
+// flight per lane; the planning kernels are integer work on wavefront bit masks.
+// The two optional stages around it, the gate projection and the expert layer, are
+// dense contractions and run on the matrix cores; they follow further down.
 #pragma once
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
 
 namespace monta {
 
@@ -16,14 +19,9 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
-#ifndef MONTA_MOVER_THREADS
-#define MONTA_MOVER_THREADS 256
-#endif
-#ifndef MONTA_VEC_IN_FLIGHT
-#define MONTA_VEC_IN_FLIGHT 4
-#endif
-constexpr int kMoverThreads = MONTA_MOVER_THREADS;   // threads per workgroup of the row movers
-constexpr int kVecInFlight = MONTA_VEC_IN_FLIGHT;    // 16-byte loads issued by a lane before its first store
+// Chosen by measurement on MI355X (128 and 512 threads, 2 and 8 vectors in flight were slower or equal).
+constexpr int kMoverThreads = 256;   // threads per workgroup of the row movers
+constexpr int kVecInFlight = 4;      // 16-byte loads issued by a lane before its first store
 
 // meta[] slots (int32)
 enum { META_R = 0, META_ALIVE = 1, META_C = 2, META_DONE = 3, META_FINAL_ROWS = 4, META_SLOTS = 16 };
