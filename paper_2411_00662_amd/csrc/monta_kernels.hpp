@@ -1611,13 +1611,17 @@ __global__ __launch_bounds__(64 * WM * WN, (64 * WM * WN <= 256 ? 2 : 1)) void e
 // registers the staged tile occupied, so 8 waves can hold a 256 x 256 tile of y (a wave 128 x 64), which halves
 // the L2 traffic per flop, and a step needs one barrier instead of two: the next step's tile streams into the other
 // of two LDS buffers while the MFMAs run.  Rows are 128 bytes in LDS without padding; the 16-byte piece c of row r
-// sits at position c ^ (r % 8), which keeps the fragment reads conflict-free; since the LDS position of a lane's
-// data is fixed by the instruction, the swizzle is applied on the global side (lane i of a chunk of 8 rows fetches
-// piece (i % 8) ^ (i / 8) of row i / 8).  Needs H to be a multiple of 64 (a tail step cannot be zero-filled on
-// this path); rows past a segment's end are fetched from its last row and their results are not stored.
-// Measured on MI355X (16384 x 4096 x 4096, one expert): 590-610 us against 715-740 us for the register-staged
-// kernel.  A segment's ragged last tile costs a full tile's time (the steps are bound by their loads, so skipping the
-// MFMAs of its empty 32-row blocks was measured and does not pay).
+// sits at position c ^ ((r / 2) % 8).  A fragment read has 16 lanes (16 consecutive rows, one piece each) share the
+// 64 banks: two rows fill them, so the pieces must differ among the even rows and among the odd rows, which r / 2
+// gives; c ^ (r % 8) makes rows r and r + 8 collide (measured with ds_read_b128 alone: 113 against 220 bytes per
+// clock and CU).  Since the LDS position of a lane's data is fixed by the instruction, the swizzle is applied on the
+// global side (lane i of a chunk of 8 rows fetches piece (i % 8) ^ ((row / 2) % 8) of tile row `row` = chunk * 8 +
+// i / 8).  Needs H to be a multiple of 64 (a tail step cannot be zero-filled on this path); rows past a segment's
+// end are fetched from its last row and their results are not stored.
+// Measured on MI355X (16384 x 4096 x 4096, one expert, bursts of 20 launches): 590-610 us against 715-740 us for the
+// register-staged kernel; with clocks settled over thousands of launches a stand-alone copy of this loop takes
+// 460-477 us.  A segment's ragged last tile costs a full tile's time (skipping the MFMAs of its empty 32-row blocks
+// was measured and does not pay).
 constexpr int kDtlBM = 256, kDtlBN = 256, kDtlWM = 2, kDtlWN = 4, kDtlThreads = 64 * kDtlWM * kDtlWN;
 constexpr int kDtlStageBytes = (kDtlBM + kDtlBN) * 128;
 constexpr int kDtlLdsBytes = 2 * kDtlStageBytes;
@@ -1628,7 +1632,7 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
     constexpr int BM = kDtlBM, BN = kDtlBN, WM = kDtlWM, WN = kDtlWN, WAVES = WM * WN;
     constexpr int CPW = (BM + BN) / 8 / WAVES;                     // 1 KiB chunks (8 tile rows) per wave and step
     constexpr int MT = BM / WM / 32, NT = BN / WN / 32;
-    static_assert((BM + BN) % (8 * WAVES) == 0 && BM % 8 == 0, "expert_dtl_kernel: chunks must divide among the waves");
+    static_assert((BM + BN) % (8 * WAVES) == 0 && BM % 16 == 0, "expert_dtl_kernel: chunks must divide among the waves");
     extern __shared__ __align__(16) unsigned char dtl_lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, m = lane & 31, g = lane >> 5;
     const int cpr = a.H / 8, nsteps = a.H / 64;
@@ -1667,12 +1671,14 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
     if (e == a.E || row0 < 0 || row0 >= row_end) return;          // surplus workgroup (uniform for the workgroup)
     const int col0 = ct * BN;
 
-    // source of this lane in each of its wave's chunks: row (chunk*8 + lane/8) of the tile, piece (lane%8)^(lane/8)
-    const int lr = lane >> 3, lc = (lane & 7) ^ lr;
+    // source of this lane in each of its wave's chunks: tile row chunk*8 + lane/8, piece (lane%8) ^ ((row/2)%8)
+    // (BM is a multiple of 16, so the rows of the weight tile swizzle like rows 0.. of their own)
+    const int lr = lane >> 3;
     const u32x4 *src[CPW];
 #pragma unroll
     for (int q = 0; q < CPW; ++q) {
         const int trow = (wave * CPW + q) * 8 + lr;
+        const int lc = (lane & 7) ^ ((trow >> 1) & 7);
         if (trow < BM) {
             const int r = row0 + trow;
             src[q] = x + (int64_t)(r < row_end ? r : row_end - 1) * cpr + lc;
@@ -1702,7 +1708,7 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
     const unsigned char *pb = dtl_lds + (size_t)(BM + wn * (BN / WN) + m) * 128;
     int koff[kExpBK / 16];                                         // byte offset of this lane's fragment piece per k-slice
 #pragma unroll
-    for (int ks = 0; ks < kExpBK / 16; ++ks) koff[ks] = ((2 * ks + g) ^ (m & 7)) * 16;
+    for (int ks = 0; ks < kExpBK / 16; ++ks) koff[ks] = ((2 * ks + g) ^ ((m >> 1) & 7)) * 16;   // 32-row blocks: (row/2)%8 = (m/2)%8
 
     issue(0, 0);
     for (int step = 0; step < nsteps; ++step) {
