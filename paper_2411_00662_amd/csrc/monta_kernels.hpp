@@ -1475,6 +1475,55 @@ struct ExpertArgs {
     int32_t grid8;          // unused
 };
 
+// The expert whose tiles include logical tile number L, found without walking the experts one by one (a walk costs
+// one dependent table read per expert before the workgroup can start): 64 experts at a time, one per lane, a wave
+// scan of their tile counts, a ballot for the first lane whose running total passes L.  Every lane of every wave
+// takes part and gets the same answer.  e == E: no such tile (a surplus workgroup).
+struct ExpertTileHit {
+    int e, lo, hi, tiles;     // expert, its row range [lo, hi), its row tiles
+    int64_t L;                // tile number inside the expert
+};
+
+template <int BM>
+__device__ __forceinline__ ExpertTileHit find_expert_tile(const ExpertArgs &a, int nct, int64_t L, int lane)
+{
+    ExpertTileHit h;
+    h.e = a.E;
+    h.lo = h.hi = h.tiles = 0;
+    h.L = 0;
+    int64_t before = 0;                                            // tiles of the experts of earlier rounds
+    for (int e0 = 0; e0 < a.E; e0 += kWave) {
+        const int e = e0 + lane;
+        int lo = 0, hi = 0, tiles = 0;
+        if (e < a.E) {
+            lo = a.lo[e];
+            hi = a.hi_base[e] + (a.hi_len ? a.hi_len[e] : 0);
+            tiles = hi > lo ? (int)(((int64_t)hi - lo + BM - 1) / BM) : 0;
+        }
+        const int64_t cnt = (int64_t)tiles * nct;
+        int64_t incl = cnt;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int64_t o = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += o;
+        }
+        const int64_t total = __shfl(incl, kWave - 1, kWave);
+        if (L < before + total) {
+            // an expert without tiles repeats its predecessor's running total, so the first lane past L has tiles
+            const unsigned long long past = __ballot(L < before + incl);
+            const int src = __ffsll((long long)past) - 1;
+            h.e = e0 + src;
+            h.lo = __shfl(lo, src, kWave);
+            h.hi = __shfl(hi, src, kWave);
+            h.tiles = __shfl(tiles, src, kWave);
+            h.L = L - before - (__shfl(incl, src, kWave) - __shfl(cnt, src, kWave));
+            return h;
+        }
+        before += total;
+    }
+    return h;
+}
+
 __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f)
 {
     const unsigned int u = __float_as_uint(f);
@@ -1499,17 +1548,13 @@ __global__ __launch_bounds__(64 * WM * WN, (64 * WM * WN <= 256 ? 2 : 1)) void e
     constexpr int kPerXcd = 32 * G::kWgsPerCu;
     const int64_t jx = blockIdx.x / kXcds;
     int64_t L = (jx / kPerXcd) * (kPerXcd * kXcds) + (int64_t)(blockIdx.x % kXcds) * kPerXcd + jx % kPerXcd;
-    int e = 0, row0 = 0, row_end = 0, ct = 0;
-    for (; e < a.E; ++e) {
-        const int lo = a.lo[e], hi = a.hi_base[e] + (a.hi_len ? a.hi_len[e] : 0);
-        const int tiles = hi > lo ? (hi - lo + BM - 1) / BM : 0;
-        if (L < (int64_t)tiles * nct) {
-            ct = (int)(L / tiles);
-            row0 = lo + (int)(L % tiles) * BM;
-            row_end = hi < a.max_rows ? hi : a.max_rows;
-            break;
-        }
-        L -= (int64_t)tiles * nct;
+    const ExpertTileHit hit = find_expert_tile<BM>(a, nct, L, lane);
+    const int e = hit.e;
+    int row0 = 0, row_end = 0, ct = 0;
+    if (e < a.E) {
+        ct = (int)(hit.L / hit.tiles);
+        row0 = hit.lo + (int)(hit.L % hit.tiles) * BM;
+        row_end = hit.hi < a.max_rows ? hit.hi : a.max_rows;
     }
     if (e == a.E || row0 < 0 || row0 >= row_end) return;          // surplus workgroup (uniform for the workgroup)
     const int col0 = ct * BN;
@@ -1645,28 +1690,24 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
     // then works on 8 row tiles x 4 column tiles at a time (12 distinct operand tiles instead of 33).
     const int64_t j = blockIdx.x / kXcds;
     int64_t L = (j / 32) * (32 * kXcds) + (int64_t)(blockIdx.x % kXcds) * 32 + j % 32;
-    int e = 0, row0 = 0, row_end = 0, ct = 0;
-    for (; e < a.E; ++e) {
-        const int lo = a.lo[e], hi = a.hi_base[e] + (a.hi_len ? a.hi_len[e] : 0);
-        const int tiles = hi > lo ? (hi - lo + BM - 1) / BM : 0;
-        if (L < (int64_t)tiles * nct) {
-            constexpr int P = 8;                                   // row tiles of a panel (4..32 measure alike)
-            const int full = tiles / P;                            // whole panels
-            int rt;
-            if (L < (int64_t)full * P * nct) {
-                const int p = (int)(L / (P * nct)), rem = (int)(L % (P * nct));
-                ct = rem / P;
-                rt = p * P + rem % P;
-            } else {
-                const int rem = (int)(L - (int64_t)full * P * nct), pr = tiles - full * P;
-                ct = rem / pr;
-                rt = full * P + rem % pr;
-            }
-            row0 = lo + rt * BM;
-            row_end = hi < a.max_rows ? hi : a.max_rows;
-            break;
+    const ExpertTileHit hit = find_expert_tile<BM>(a, nct, L, lane);
+    const int e = hit.e;
+    int row0 = 0, row_end = 0, ct = 0;
+    if (e < a.E) {
+        constexpr int P = 8;                                       // row tiles of a panel (4..32 measure alike)
+        const int tiles = hit.tiles, full = tiles / P;             // whole panels
+        int rt;
+        if (hit.L < (int64_t)full * P * nct) {
+            const int p = (int)(hit.L / (P * nct)), rem = (int)(hit.L % (P * nct));
+            ct = rem / P;
+            rt = p * P + rem % P;
+        } else {
+            const int rem = (int)(hit.L - (int64_t)full * P * nct), pr = tiles - full * P;
+            ct = rem / pr;
+            rt = full * P + rem % pr;
         }
-        L -= (int64_t)tiles * nct;
+        row0 = hit.lo + rt * BM;
+        row_end = hit.hi < a.max_rows ? hit.hi : a.max_rows;
     }
     if (e == a.E || row0 < 0 || row0 >= row_end) return;          // surplus workgroup (uniform for the workgroup)
     const int col0 = ct * BN;

@@ -92,6 +92,9 @@ CASES = [
     # a ragged second column tile, the padded layout
     (4096, 128, 3, 2, 3, 2, 2, 0.9, 264, 0),
     (3072, 192, 2, 2, 1, 1, 3, 0.7, 512, 1),
+    # more than 64 experts (the tile lookup takes two rounds of 64), with both kernels
+    (2000, 72, 100, 2, 4, 1, 2, 0.0, 40, 0),
+    (10240, 64, 80, 2, 4, 2, 2, 0.0, 256, 0),
 ]
 
 
