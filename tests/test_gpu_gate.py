@@ -132,26 +132,60 @@ def test_gate_named_workloads_full_size(m, name):
 
 
 def test_gate_feeds_the_routing_path(m):
-    """Gate -> route/dispatch/regather -> combine on the GPU; the oracle runs the same path from the GPU's
-    logits (its own logits may differ in the last bits and flip a near-tie, which says nothing about routing)."""
+    """Gate -> route/dispatch/regather -> combine on the GPU against the oracle run from its OWN logits.
+
+    A GPU logit may differ from the oracle's within the projection's tolerance, which can flip a choice only where two
+    logits of a token are closer than that.  So: tokens whose top-(k+1) logits are further apart than the tolerance
+    ("decided", all but a few) must get the oracle's experts in the oracle's order; for the others the chosen experts
+    must be within tolerance of the oracle's k-th logit; and when no choice flipped (the expected outcome: the
+    worst-case tolerance is far above the error of a real fp32 sum) every table and buffer must match."""
     import torch
     from paper_2411_00662_amd import buffers as bufs
     w = Workload("g2r", 1024, 512, BF16, 16, 2, 4, 2, 2, 1.0)
+    k = w.top_k
     _, x = workloads.make_inputs(w, seed=11)
     wg = workloads.make_gate_weights(w, seed=11)
-    cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor)
+    logits = oracle.gate(x, wg)
+    ref = oracle.forward(logits, x, k=k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor)
+    R = ref.plan.R
+    assert 0 < R < w.tokens * k                  # the case has drops
+
+    cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, k, w.ep, w.tp, w.slices, w.capacity_factor)
     b = m.alloc_buffers(cfg, None, x, canary=0xA5)
     wd = bufs.to_device_act(cfg, wg)
     m.monta_gate(cfg, b.x, wd, b.logits)
     m.monta_route_dispatch_regather(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, b.ws)
     m.monta_combine(cfg, b.final, b.gates, b.out, b.ws)
     torch.cuda.synchronize()
-    logits = b.logits.cpu().numpy()
-    ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor)
-    np.testing.assert_array_equal(b.topk_idx.cpu().numpy(), ref.topk_idx)
-    R = ref.plan.R
-    assert 0 < R < w.tokens * w.top_k            # the case has drops
-    np.testing.assert_array_equal(bufs.to_host_act(cfg, b.final)[:R], ref.final[:R])
-    same = np.all(b.gates.cpu().numpy() == ref.gates, axis=1)
-    assert same.mean() > 0.5
-    np.testing.assert_array_equal(bufs.to_host_act(cfg, b.out)[same], ref.out[same])
+    got_idx = b.topk_idx.cpu().numpy()
+
+    l64 = logits.astype(np.float64)
+    tol = w.hidden * 2.0 ** -24 * (np.abs(as_f64(x, BF16)) @ np.abs(as_f64(wg, BF16)).T) + 2.0 ** -24 * np.abs(l64)
+    order = np.argsort(-l64, axis=1, kind="stable")
+    srt = np.take_along_axis(l64, order, axis=1)
+    tsrt = np.take_along_axis(tol, order, axis=1)
+    gaps = srt[:, :k] - srt[:, 1:k + 1]                                  # between ranks j and j+1, j < k
+    decided = np.all(gaps > tsrt[:, :k] + tsrt[:, 1:k + 1], axis=1)
+    assert decided.mean() > 0.95
+    np.testing.assert_array_equal(got_idx[decided], ref.topk_idx[decided])
+    # undecided tokens: every chosen expert is within tolerance of the oracle's k-th largest logit
+    rows = np.nonzero(~decided)[0]
+    for t in rows:
+        kth = srt[t, k - 1]
+        for e in got_idx[t]:
+            assert l64[t, e] >= kth - (tol[t, e] + tsrt[t, k - 1]), (t, e)
+        assert len(set(got_idx[t].tolist())) == k
+
+    if np.array_equal(got_idx, ref.topk_idx):
+        tabs = m.read_tables(cfg, b.ws)
+        assert tabs["R"] == R
+        np.testing.assert_array_equal(tabs["pos_final"], ref.plan.pos_final)
+        np.testing.assert_array_equal(bufs.to_host_act(cfg, b.final)[:R], ref.final[:R])
+        # gates come from logits that differ within tol: softmax moves by at most the largest logit difference
+        gd = np.abs(b.gates.cpu().numpy().astype(np.float64) - ref.gates.astype(np.float64))
+        assert np.all(gd <= 2.0 * tol.max(axis=1, keepdims=True) + 1e-6)
+        d = np.abs(workloads.bf16_bits_to_f32(bufs.to_host_act(cfg, b.out)).astype(np.float64)
+                   - workloads.bf16_bits_to_f32(ref.out).astype(np.float64))
+        assert d.max() <= 1e-2                   # the bf16 bar of the combine step
+    else:
+        _say("a near-tie flipped between the two gate projections: buffers not compared")
