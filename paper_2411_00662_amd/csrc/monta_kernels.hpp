@@ -1472,7 +1472,7 @@ struct ExpertArgs {
     const int32_t *hi_base; // [E] one past its last row is hi_base[e] + hi_len[e] ...
     const int32_t *hi_len;  // [E] ... or hi_base[e] alone if this is nullptr
     int32_t E, H, N, max_rows;
-    int32_t grid8;          // unused
+    int32_t reserved;       // unused
 };
 
 // The expert whose tiles include logical tile number L, found without walking the experts one by one (a walk costs
@@ -1484,8 +1484,11 @@ struct ExpertTileHit {
     int64_t L;                // tile number inside the expert
 };
 
-template <int BM>
-__device__ __forceinline__ ExpertTileHit find_expert_tile(const ExpertArgs &a, int nct, int64_t L, int lane)
+// WHOLE: only the whole tiles of a segment count (its ragged last tile is numbered elsewhere); `all` returns the
+// number of tiles counted over all experts when L lies past them.
+template <int BM, bool WHOLE = false>
+__device__ __forceinline__ ExpertTileHit find_expert_tile(const ExpertArgs &a, int nct, int64_t L, int lane,
+                                                          int64_t *all = nullptr)
 {
     ExpertTileHit h;
     h.e = a.E;
@@ -1498,7 +1501,7 @@ __device__ __forceinline__ ExpertTileHit find_expert_tile(const ExpertArgs &a, i
         if (e < a.E) {
             lo = a.lo[e];
             hi = a.hi_base[e] + (a.hi_len ? a.hi_len[e] : 0);
-            tiles = hi > lo ? (int)(((int64_t)hi - lo + BM - 1) / BM) : 0;
+            tiles = hi > lo ? (int)(((int64_t)hi - lo + (WHOLE ? 0 : BM - 1)) / BM) : 0;
         }
         const int64_t cnt = (int64_t)tiles * nct;
         int64_t incl = cnt;
@@ -1521,6 +1524,7 @@ __device__ __forceinline__ ExpertTileHit find_expert_tile(const ExpertArgs &a, i
         }
         before += total;
     }
+    if (all) *all = before;
     return h;
 }
 
@@ -1671,6 +1675,7 @@ constexpr int kDtlBM = 256, kDtlBN = 256, kDtlWM = 2, kDtlWN = 4, kDtlThreads = 
 constexpr int kDtlStageBytes = (kDtlBM + kDtlBN) * 128;
 constexpr int kDtlLdsBytes = 2 * kDtlStageBytes;
 
+template <bool RAGGED_LAST>
 __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
                                                                  unsigned short *__restrict__ y, ExpertArgs a)
 {
@@ -1690,8 +1695,15 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
     // then works on 8 row tiles x 4 column tiles at a time (12 distinct operand tiles instead of 33).
     const int64_t j = blockIdx.x / kXcds;
     int64_t L = (j / 32) * (32 * kXcds) + (int64_t)(blockIdx.x % kXcds) * 32 + j % 32;
-    const ExpertTileHit hit = find_expert_tile<BM>(a, nct, L, lane);
-    const int e = hit.e;
+    // With RAGGED_LAST the whole tiles of all experts are numbered first and the ragged last tiles of the segments
+    // after them, the one with the most rows first: a launch rarely fills its last round of workgroups, and this way
+    // that round consists of the tiles that cost least (their empty 32-row blocks are skipped below).  The price: a
+    // ragged tile no longer shares its weight tile's trip through the L2 with the other row tiles of its panel, so
+    // the host asks for it only when the ragged tiles are few (at most one round of workgroups).
+    int64_t whole = 0;
+    const ExpertTileHit hit = RAGGED_LAST ? find_expert_tile<BM, true>(a, nct, L, lane, &whole)
+                                          : find_expert_tile<BM, false>(a, nct, L, lane);
+    int e = hit.e;
     int row0 = 0, row_end = 0, ct = 0;
     if (e < a.E) {
         constexpr int P = 8;                                       // row tiles of a panel (4..32 measure alike)
@@ -1708,6 +1720,37 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
         }
         row0 = hit.lo + rt * BM;
         row_end = hit.hi < a.max_rows ? hit.hi : a.max_rows;
+    } else if (RAGGED_LAST) {
+        // ragged tiles: position L / nct in the order (rows in the ragged tile, descending; expert, ascending).  The
+        // tile buffers are not in use yet, so their first bytes serve as the scratch of the ranking (E <= 256).
+        const int64_t Lr = L - whole;
+        int *scr = reinterpret_cast<int *>(dtl_lds);
+        int my_rem = 0;
+        if (tid < a.E) {
+            const int lo = a.lo[tid], hi = a.hi_base[tid] + (a.hi_len ? a.hi_len[tid] : 0);
+            my_rem = hi > lo ? (int)(((int64_t)hi - lo) % BM) : 0;
+            scr[tid] = my_rem;
+        }
+        if (tid == 0) scr[256] = -1;
+        __syncthreads();
+        if (my_rem > 0) {
+            int rank = 0;
+            for (int o = 0; o < a.E; ++o) {
+                const int ro = scr[o];
+                rank += (ro > my_rem || (ro == my_rem && o < tid)) ? 1 : 0;
+            }
+            if (rank == Lr / nct) scr[256] = tid;
+        }
+        __syncthreads();
+        const int eh = scr[256];
+        __syncthreads();                                           // everyone has read it before the tiles stream in
+        if (eh >= 0 && eh < a.E) {
+            e = eh;
+            const int lo = a.lo[e], hi = a.hi_base[e] + (a.hi_len ? a.hi_len[e] : 0);
+            ct = (int)(Lr % nct);
+            row0 = lo + (int)(((int64_t)hi - lo) / BM) * BM;
+            row_end = hi < a.max_rows ? hi : a.max_rows;
+        }
     }
     if (e == a.E || row0 < 0 || row0 >= row_end) return;          // surplus workgroup (uniform for the workgroup)
     const int col0 = ct * BN;
@@ -1716,10 +1759,12 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
     // (BM is a multiple of 16, so the rows of the weight tile swizzle like rows 0.. of their own)
     const int lr = lane >> 3;
     const u32x4 *src[CPW];
+    unsigned skip = 0;                      // chunks of 8 rows of x wholly past the segment's end: never fetched
 #pragma unroll
     for (int q = 0; q < CPW; ++q) {
         const int trow = (wave * CPW + q) * 8 + lr;
         const int lc = (lane & 7) ^ ((trow >> 1) & 7);
+        if (RAGGED_LAST && (wave * CPW + q) * 8 < BM && row0 + (wave * CPW + q) * 8 >= row_end) skip |= 1u << q;
         if (trow < BM) {
             const int r = row0 + trow;
             src[q] = x + (int64_t)(r < row_end ? r : row_end - 1) * cpr + lc;
@@ -1729,11 +1774,20 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
         }
     }
     auto issue = [&](int step, int buf) {
+        if (skip == 0) {
 #pragma unroll
-        for (int q = 0; q < CPW; ++q)
-            __builtin_amdgcn_global_load_lds(
-                (const void __attribute__((address_space(1))) *)(src[q] + step * 8),
-                (void __attribute__((address_space(3))) *)(dtl_lds + buf * kDtlStageBytes + (wave * CPW + q) * 1024), 16, 0, 0);
+            for (int q = 0; q < CPW; ++q)
+                __builtin_amdgcn_global_load_lds(
+                    (const void __attribute__((address_space(1))) *)(src[q] + step * 8),
+                    (void __attribute__((address_space(3))) *)(dtl_lds + buf * kDtlStageBytes + (wave * CPW + q) * 1024), 16, 0, 0);
+        } else {
+#pragma unroll
+            for (int q = 0; q < CPW; ++q)
+                if (!((skip >> q) & 1u))
+                    __builtin_amdgcn_global_load_lds(
+                        (const void __attribute__((address_space(1))) *)(src[q] + step * 8),
+                        (void __attribute__((address_space(3))) *)(dtl_lds + buf * kDtlStageBytes + (wave * CPW + q) * 1024), 16, 0, 0);
+        }
     };
 
     f32x16 acc[MT][NT];
@@ -1751,6 +1805,13 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
 #pragma unroll
     for (int ks = 0; ks < kExpBK / 16; ++ks) koff[ks] = ((2 * ks + g) ^ ((m >> 1) & 7)) * 16;   // 32-row blocks: (row/2)%8 = (m/2)%8
 
+    // 32-row blocks of this wave that hold rows of the segment (all MT of them except in a ragged tile)
+    int nb = MT;
+    if (RAGGED_LAST) {
+        nb = (row_end - row0 - wm * (BM / WM) + 31) / 32;
+        nb = nb < 0 ? 0 : (nb > MT ? MT : nb);
+    }
+
     issue(0, 0);
     for (int step = 0; step < nsteps; ++step) {
         // s_waitcnt vmcnt(0) (expcnt and lgkmcnt left at their maxima): this step's tile has landed in LDS
@@ -1758,18 +1819,38 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
         __syncthreads();                                           // ... for every wave, and the other buffer is free
         if (step + 1 < nsteps) issue(step + 1, (step + 1) & 1);    // streams in during the MFMAs
         const int buf = (step & 1) * kDtlStageBytes;
+        if (nb == MT) {
 #pragma unroll
-        for (int ks = 0; ks < kExpBK / 16; ++ks) {
-            bf16x8 fa[MT], fb[NT];
+            for (int ks = 0; ks < kExpBK / 16; ++ks) {
+                bf16x8 fa[MT], fb[NT];
 #pragma unroll
-            for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const bf16x8 *>(pa + buf + i * 32 * 128 + koff[ks]);
+                for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const bf16x8 *>(pa + buf + i * 32 * 128 + koff[ks]);
 #pragma unroll
-            for (int j = 0; j < NT; ++j) fb[j] = *reinterpret_cast<const bf16x8 *>(pb + buf + j * 32 * 128 + koff[ks]);
+                for (int j = 0; j < NT; ++j) fb[j] = *reinterpret_cast<const bf16x8 *>(pb + buf + j * 32 * 128 + koff[ks]);
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
+                for (int i = 0; i < MT; ++i)
 #pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < NT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
+        } else if (nb > 0) {
+            // ragged tile: blocks past the segment's end are not multiplied (uniform per wave); the fragment reads stay
+            // as they are, so that the loop keeps the shape of the one above (what they fetch there is never used)
+#pragma unroll
+            for (int ks = 0; ks < kExpBK / 16; ++ks) {
+                bf16x8 fa[MT], fb[NT];
+#pragma unroll
+                for (int i = 0; i < MT; ++i) fa[i] = *reinterpret_cast<const bf16x8 *>(pa + buf + i * 32 * 128 + koff[ks]);
+#pragma unroll
+                for (int j = 0; j < NT; ++j) fb[j] = *reinterpret_cast<const bf16x8 *>(pb + buf + j * 32 * 128 + koff[ks]);
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+                    if (i < nb) {
+#pragma unroll
+                        for (int j = 0; j < NT; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    }
+            }
         }
     }
 

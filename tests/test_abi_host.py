@@ -165,3 +165,16 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2411_00662_amd" not in text and "libmonta.so" not in text
+
+
+def test_build_refuses_kernels_that_spill():
+    """The build reads the compiler's resource-usage remarks and names every kernel that uses scratch memory."""
+    from paper_2411_00662_amd.build import scratch_users
+    remarks = (
+        "k.hpp:1:0: remark: Function Name: kernel_a [-Rpass-analysis=kernel-resource-usage]\n"
+        "k.hpp:1:0: remark:     VGPRs: 256 [-Rpass-analysis=kernel-resource-usage]\n"
+        "k.hpp:1:0: remark:     ScratchSize [bytes/lane]: 352 [-Rpass-analysis=kernel-resource-usage]\n"
+        "k.hpp:9:0: remark: Function Name: kernel_b [-Rpass-analysis=kernel-resource-usage]\n"
+        "k.hpp:9:0: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n")
+    assert scratch_users(remarks) == [("kernel_a", 352)]
+    assert scratch_users("") == []

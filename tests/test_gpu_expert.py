@@ -95,6 +95,8 @@ CASES = [
     # more than 64 experts (the tile lookup takes two rounds of 64), with both kernels
     (2000, 72, 100, 2, 4, 1, 2, 0.0, 40, 0),
     (10240, 64, 80, 2, 4, 2, 2, 0.0, 256, 0),
+    # many ragged tiles (experts x column tiles above one round of workgroups): they stay inside their segments' panels
+    (10240, 64, 80, 2, 4, 2, 2, 0.0, 1024, 0),
 ]
 
 
