@@ -1675,6 +1675,89 @@ constexpr int kDtlBM = 256, kDtlBN = 256, kDtlWM = 2, kDtlWN = 4, kDtlThreads = 
 constexpr int kDtlStageBytes = (kDtlBM + kDtlBN) * 128;
 constexpr int kDtlLdsBytes = 2 * kDtlStageBytes;
 
+// A ragged tile of at most 64 rows, the kind a launch's last round is made of: so little arithmetic per step that the
+// step is as long as its loads take to arrive.  Compact stages of 64 + 256 rows (40 KiB), three of them, the loads of
+// two steps in flight: half the time per step of the two-stage loop.  Eight waves, each all 64 rows x 32 columns.
+// Every wave issues the same number of loads per step (rows past the segment's end repeat its last row), because the
+// wait for a stage counts the younger loads.  The barrier is the bare instruction behind a wait for the LDS reads: the
+// compiler's own barrier would wait for every outstanding load, the next stages' included.
+__device__ __forceinline__ void expert_dtl_small_rows(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
+                                                      unsigned short *__restrict__ y, const ExpertArgs &a, int e,
+                                                      int row0, int row_end, int col0, unsigned char *lds)
+{
+    constexpr int XR = 64, WR = 256, STG = (XR + WR) * 128, NST = 3, CPW = (XR + WR) / 8 / 8;   // 5 chunks per wave
+    static_assert(NST * STG <= kDtlLdsBytes && XR % 16 == 0, "expert_dtl_small_rows: stages must fit the kernel's LDS");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, m = lane & 31, g = lane >> 5;
+    const int cpr = a.H / 8, nsteps = a.H / 64;
+    const int lr = lane >> 3;
+    const u32x4 *src[CPW];
+#pragma unroll
+    for (int q = 0; q < CPW; ++q) {
+        const int trow = (wave * CPW + q) * 8 + lr;                // 0 .. 319
+        const int lc = (lane & 7) ^ ((trow >> 1) & 7);
+        if (trow < XR) {
+            const int r = row0 + trow;
+            src[q] = x + (int64_t)(r < row_end ? r : row_end - 1) * cpr + lc;
+        } else {
+            const int n = col0 + trow - XR;
+            src[q] = w + ((int64_t)e * a.N + (n < a.N ? n : a.N - 1)) * cpr + lc;
+        }
+    }
+    auto issue = [&](int step, int slot) {
+#pragma unroll
+        for (int q = 0; q < CPW; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1))) *)(src[q] + step * 8),
+                (void __attribute__((address_space(3))) *)(lds + slot * STG + (wave * CPW + q) * 1024), 16, 0, 0);
+    };
+    f32x16 acc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    const unsigned char *pa = lds + (size_t)m * 128;
+    const unsigned char *pb = lds + (size_t)(XR + wave * 32 + m) * 128;
+    int koff[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) koff[ks] = ((2 * ks + g) ^ ((m >> 1) & 7)) * 16;
+    const int nb = row_end - row0 > 32 ? 2 : 1;                    // 32-row blocks with rows of the segment
+
+    issue(0, 0);
+    if (nsteps > 1) issue(1, 1);
+    int slot = 0;
+    for (int step = 0; step < nsteps; ++step) {
+        // stage `step` has landed once at most the CPW loads of stage step+1 are outstanding (loads finish in order)
+        if (step + 1 < nsteps) __builtin_amdgcn_s_waitcnt(0x0f70 | CPW);
+        else __builtin_amdgcn_s_waitcnt(0x0f70);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xc07f);                        // lgkmcnt(0): this wave's reads of the previous stage
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (step + 2 < nsteps) issue(step + 2, slot == 0 ? 2 : slot - 1);   // the slot of stage step-1, free now
+        const int buf = slot * STG;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 fb = *reinterpret_cast<const bf16x8 *>(pb + buf + koff[ks]);
+            const bf16x8 fa0 = *reinterpret_cast<const bf16x8 *>(pa + buf + koff[ks]);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb, acc[0], 0, 0, 0);
+            if (nb > 1) {
+                const bf16x8 fa1 = *reinterpret_cast<const bf16x8 *>(pa + buf + 32 * 128 + koff[ks]);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb, acc[1], 0, 0, 0);
+            }
+        }
+        slot = slot == 2 ? 0 : slot + 1;
+    }
+    const int n = col0 + wave * 32 + m;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = row0 + i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+            if (r < row_end && n < a.N) y[(int64_t)r * a.N + n] = (unsigned short)f32_to_bf16_rne(acc[i][v]);
+        }
+}
+
+
 template <bool RAGGED_LAST>
 __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__restrict__ x, const u32x4 *__restrict__ w,
                                                                  unsigned short *__restrict__ y, ExpertArgs a)
@@ -1754,6 +1837,10 @@ __global__ __launch_bounds__(kDtlThreads) void expert_dtl_kernel(const u32x4 *__
     }
     if (e == a.E || row0 < 0 || row0 >= row_end) return;          // surplus workgroup (uniform for the workgroup)
     const int col0 = ct * BN;
+    if (RAGGED_LAST && row_end - row0 <= 64) {                     // a short ragged tile: the three-stage loop
+        expert_dtl_small_rows(x, w, y, a, e, row0, row_end, col0, dtl_lds);
+        return;
+    }
 
     // source of this lane in each of its wave's chunks: tile row chunk*8 + lane/8, piece (lane%8) ^ ((row/2)%8)
     // (BM is a multiple of 16, so the rows of the weight tile swizzle like rows 0.. of their own)

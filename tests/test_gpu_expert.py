@@ -191,6 +191,35 @@ def test_expert_random_shapes_bit_exact(m):
         np.testing.assert_array_equal(got2[rows], want[rows], err_msg=str(case))
 
 
+@pytest.mark.parametrize("H", [64, 128, 320])
+def test_expert_short_and_long_ragged_tiles(m, H):
+    """Segment sizes fixed by the logits (top-1, one expert per token run): 2 whole tiles + 7 rows, 1 whole tile + 64
+    rows (the longest "short" ragged tile), 2 whole tiles + 249 rows, and 33 rows alone.  Hidden sizes of one, two and
+    five 64-element steps take the short-tile loop through its start-up, its last steps and a full turn of its three
+    stages.  Small integers: exact."""
+    sizes = [2 * 256 + 7, 256 + 64, 2 * 256 + 249, 33]
+    T, E, N = sum(sizes), 4, 264
+    _say(f"expert ragged tiles H={H} sizes={sizes}")
+    w = Workload("ex-ragged", T, H, BF16, E, 1, 2, 1, 1, 0.0)
+    logits = np.full((T, E), -4.0, np.float32)
+    t0 = 0
+    for e, n in enumerate(sizes):
+        logits[t0:t0 + n, e] = 4.0
+        t0 += n
+    rng = np.random.default_rng(H)
+    logits += rng.uniform(-0.25, 0.25, size=logits.shape).astype(np.float32)
+    x = to_act(rng.integers(-4, 5, size=(T, H)).astype(np.float32), BF16)
+    we = to_act(rng.integers(-4, 5, size=(E, N, H)).astype(np.float32), BF16)
+    cfg, b, ref = run_path(m, w, logits, x)
+    pl = ref.plan
+    assert [int(v) for v in pl.kept] == sizes
+    lo, hi = oracle.expert_ranges(pl, w.tp, w.slices)
+    want = oracle.expert(ref.final, we, lo, hi)
+    got, _ = expert_gpu(m, cfg, b, we, N)
+    rows = check_untouched(got, pl)
+    np.testing.assert_array_equal(got[rows], want[rows])
+
+
 def test_expert_identity_weights_reproduce_the_identity_expert_path(m):
     """w[e] = I: y equals FINAL on the kept rows, and combine of y equals combine of FINAL."""
     import torch
