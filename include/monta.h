@@ -44,7 +44,9 @@
  * e / (experts / ep), so expert order is (EP rank, local expert) order.
  *
  * Buffers.  STAGE and FINAL hold `max_rows` rows of hidden elements; only rows
- * below R (the number of kept pairs) are ever written.
+ * below R (the number of kept pairs) are ever written -- except in the
+ * capacity-padded layout (cfg->padded = 1), where FINAL is written up to row
+ * E*C: kept rows first in every expert's block, zeros behind them.
  *   STAGE  [slice][tp rank][expert][kept rows of that unit, token order]
  *   FINAL  [expert][kept rows, token order]
  */
@@ -91,7 +93,8 @@ typedef struct monta_cfg {
 /* Where the plan tables live inside the caller's workspace (byte offsets from
  * `ws`; every table is int32, row-major).  Filled by monta_ws_layout_query(). */
 typedef struct monta_ws_layout {
-    int64_t ws_bytes;        /* size the caller must allocate (256-byte aligned base)           */
+    int64_t ws_bytes;        /* size the caller must allocate; the base must be 16-byte aligned (checked:
+                                MONTA_ERR_ALIGN), tables inside start at multiples of 256 bytes */
     int64_t max_rows;        /* rows STAGE / FINAL / expert output must hold: min(T*k, E*C), or E*C if padded */
     int64_t capacity;        /* C                                                               */
     int32_t units;           /* U                                                               */
@@ -213,15 +216,16 @@ int monta_route_dispatch_regather(const monta_cfg *cfg, const float *logits, con
                                   float *gates, void *stage, void *final_, void *ws, void *stream);
 
 /* Unpermutation with scale-add: out[t][:] = sum over kept j (ascending) of
- * gates[t][j] * y[pos_final[t][j]][:], accumulated in fp32 with fused
- * multiply-adds and rounded once (nearest-even) to cfg->dtype; a token with no
- * kept pair gives a zero row.  y [max_rows][H] is the expert output in FINAL
+ * gates[t][j] * y[pos_final[t][j]][:], accumulated in fp64 starting from +0 (every
+ * product of an fp32 gate with an fp32 / bf16 element is exact there) and rounded
+ * once, nearest-even, to cfg->dtype (bf16 through a round-to-odd fp32 step, so there
+ * is no double rounding); a token with no kept pair gives a zero row.  y [max_rows][H] is the expert output in FINAL
  * layout (FINAL itself under identity experts), out [T][H]. */
 int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void *out, const void *ws,
                   void *stream);
 
-/* ---- the second AllToAll, mirrored (section "Pipelining": "The same method can be applied to the
- * second AllToAll") ----
+/* ---- the second AllToAll, mirrored (section "Pipelining", end of the paragraph on the Drop / AllGather
+ * transform: the paper applies the same split to the second AllToAll) ----
  * The expert output y [max_rows][H] (FINAL layout) travels back the way the tokens came: block by
  * block into the unit-major layout of STAGE, so that every virtual TP rank again carries only 1/tp
  * of a slice, and from there into token order.  The result is bit-identical to monta_combine. */

@@ -259,9 +259,9 @@ int monta_oracle_pack(int64_t T, int k, int tp, int S, int64_t row_bytes, const 
     return ORACLE_OK;
 }
 
-/* Intra-node gather + D2D copy "to the corresponding positions based on index
- * offsets" (paragraph "AllGather and D2D copy Pipelining"): every (unit, expert)
- * block of STAGE goes to its place in the expert-major FINAL buffer. */
+/* Intra-node gather + D2D copy to the rows' index offsets (paragraph "AllGather and
+ * D2D copy Pipelining", Fig. 7-8): every (unit, expert) block of STAGE goes to its
+ * place in the expert-major FINAL buffer. */
 /* The padded layout's padding rows [offsets[e] + kept[e], offsets[e+1]) are zero-filled. */
 int monta_oracle_pad(int E, int64_t row_bytes, const int32_t *kept, const int32_t *offsets, void *final_)
 {
@@ -366,7 +366,8 @@ int monta_oracle_allgather(int tp, int S, int E, int64_t row_bytes, const int32_
 
 /* ------------------------------------------------- the second AllToAll, mirrored */
 
-/* Section "Pipelining": "The same method can be applied to the second AllToAll".  After the experts
+/* Section "Pipelining" (end of the Drop / AllGather paragraph: the split also applies to the second
+ * AllToAll).  After the experts
  * the rows travel back: the expert output y (FINAL layout, expert-major) is cut into the same
  * (unit, expert) blocks and each block returns to its place in the unit-major layout of STAGE --
  * the inverse of the gather + D2D copy -- so that every virtual TP rank again carries only 1/t of a
