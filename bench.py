@@ -6,14 +6,18 @@ already resident in HBM: monta_route (top-k, gates, counting-sort plan) ->
 monta_dispatch_regather (S-slice pack / regather pipeline) -> monta_combine
 (identity experts: the expert output is FINAL).
 
-Prints ONE JSON line.  `value` is tokens/s of the whole job; `roofline` is the
-dominant kernel's algorithmic bytes per launch over its average launch duration,
-measured here with HIP events on the launching stream; `cpu_baseline` is the CPU
-oracle timed on this host.
+The default workload is the largest one that fits one GPU (`skewed`: 65536 tokens
+of 7168 bf16, 64 experts, top-8, capacity drops).  Prints ONE JSON line.  `value`
+is tokens/s of the whole job on that workload; `roofline` is the dominant kernel's
+algorithmic bytes per launch over its average launch duration, measured here with
+HIP events on the launching stream; `cpu_baseline` is the CPU oracle timed on this
+host (all cores, and one thread); `other_configs` repeats the step timing, briefly,
+on the other named workloads so that one run shows all of them.
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -54,69 +58,33 @@ def algorithmic_bytes(w, tabs):
     return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", default="mixtral", help="tiny | mixtral | 2x70b | longctx | skewed")
-    ap.add_argument("--slices", type=int, default=0, help="override the workload's slice count")
-    ap.add_argument("--mode", type=int, default=-1, help="pipeline realisation 0/1/2 (default: library default)")
-    ap.add_argument("--graph", type=int, default=0, help="replay the step from a captured HIP graph (1) or launch eagerly (0)")
-    ap.add_argument("--calib-copy-mib", type=int, default=0,
-                    help="also run the plain copy kernel on buffers of this size (profiler byte-counter calibration)")
-    ap.add_argument("--return-path", default="direct", choices=["direct", "mirror"],
-                    help="direct: combine reads the expert output in FINAL layout (the headline path); mirror: the "
-                         "second AllToAll mirrored (unregather + staged combine pipeline), 2R more rows moved")
-    ap.add_argument("--padded", type=int, default=0, help="1: capacity-padded [E][C][H] layout of FINAL (zero-filled padding)")
-    ap.add_argument("--gate", type=int, default=0,
-                    help="1: the step starts one stage earlier, at the gate projection (monta_gate: logits = x * w_gate^T "
-                         "with random-init weights); 0: at the logits, as the headline metric is defined")
-    ap.add_argument("--experts", type=int, default=0,
-                    help="1: a real expert layer (monta_route_dispatch_expert: one H x H linear layer per expert, random-init "
-                         "weights) sits between dispatch and combine instead of identity experts")
-    ap.add_argument("--expert-overlap", type=int, default=0,
-                    help="with --experts 1: 1 = each slice's expert launch overlaps the next slice's movers (second stream)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
-    args = ap.parse_args()
+def mode_label(mode):
+    return "auto" if mode < 0 else str(mode)
 
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build covers one GPU's share of the path; nothing crosses GPUs, so only --gpus 1 is "
-              "supported (virtual EP/TP ranks are buffer partitions on one MI355X).", file=sys.stderr)
-        sys.exit(2)
 
+def measure(args, w, steps, warmup, full):
+    """Times `steps` steps of workload w.  full: also the per-kernel event pass and everything the headline line
+    carries; otherwise only the step time and the byte accounting."""
     import torch
     import workloads
     import paper_2411_00662_amd as m
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    m.binding.lib()     # no fallback: fails here if the HIP library is not built
-
-    w = workloads.CONFIGS[args.config]
-    if args.slices:
-        w = w.with_(slices=args.slices)
-    if args.padded:
-        w = w.with_(padded=1)
-    if args.mode >= 0:
-        m.monta_set_pipeline_mode(args.mode)
     mode = m.monta_get_pipeline_mode()
     logits, x = workloads.make_inputs(w)
     cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm,
                      w.padded)
     b = m.alloc_buffers(cfg, logits, x)
-
     stream = torch.cuda.Stream()          # default priority; the whole step is enqueued on it
 
-    mirror = args.return_path == "mirror"
+    mirror = full and args.return_path == "mirror"
+    gate = full and args.gate
+    experts = full and args.experts
     y_stage = torch.empty_like(b.stage) if mirror else None
-    w_gate_host = workloads.make_gate_weights(w) if args.gate else None
-    w_gate = m.buffers.to_device_act(cfg, w_gate_host) if args.gate else None
+    w_gate_host = workloads.make_gate_weights(w) if gate else None
+    w_gate = m.buffers.to_device_act(cfg, w_gate_host) if gate else None
 
     w_exp = y_exp = None
-    if args.experts:
+    if experts:
         if w.dtype != workloads.BF16:
             print("bench.py: --experts needs a bf16 workload", file=sys.stderr)
             sys.exit(2)
@@ -127,9 +95,9 @@ def main():
         y_exp = torch.empty_like(b.final)
 
     def step():
-        if args.gate:
+        if gate:
             m.monta_gate(cfg, b.x, w_gate, b.logits, stream)
-        if args.experts:
+        if experts:
             m.monta_route_dispatch_expert(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, w_exp, w.hidden, y_exp,
                                           b.ws, args.expert_overlap, stream)
             m.monta_combine(cfg, y_exp, b.gates, b.out, b.ws, stream)
@@ -141,8 +109,7 @@ def main():
             m.monta_combine(cfg, b.final, b.gates, b.out, b.ws, stream)
 
     torch.cuda.synchronize()
-    use_graph = bool(args.graph)
-    graph = None
+    use_graph = full and bool(args.graph)
     with torch.cuda.stream(stream):
         step()                              # first touch, also creates the side stream before any capture
         stream.synchronize()
@@ -153,16 +120,15 @@ def main():
             run = graph.replay
         else:
             run = step
-        for _ in range(args.warmup):
+        for _ in range(warmup):
             run()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             run()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    tokens_per_s = w.tokens / (ms_per_step * 1e-3)
+    ms_per_step = (t1 - t0) * 1e3 / steps
 
     def time_eager(n):
         with torch.cuda.stream(stream):
@@ -186,20 +152,23 @@ def main():
         ab["total"] += 2 * ab["R"] * ab["row"]
         ab["unregather_s"] = ab["regather_s"]
         ab["combine_s"] = [ab["regather_s"][j] // 2 + (w.tokens // w.slices) * ab["row"] for j in range(w.slices)]
-    if args.gate:
+    if gate:
         ab["gate"] = (w.tokens + w.experts) * ab["row"] + w.tokens * w.experts * 4
         ab["total"] += ab["gate"]
-    if args.experts:
+    if experts:
         ab["expert_flops"] = 2.0 * ab["R"] * w.hidden * w.hidden
         ab["expert"] = (2 * ab["R"] + w.experts * w.hidden) * ab["row"]       # rows read and written once, weights once
         ab["total"] += ab["expert"]
-    eff_gbps = ab["total"] / (ms_per_step * 1e-3) / 1e9
+    res = {"ms_per_step": ms_per_step, "ab": ab, "mode": mode, "use_graph": use_graph, "roofline": None, "kernels": {},
+           "inputs": (logits, x), "w_gate_host": w_gate_host}
+    if not full:
+        del b
+        return res
 
     # ---- per-kernel durations: HIP events around every launch, on the launching stream, eager launches
-    roofline = None
     kernels = {}
     if not args.no_profile:
-        prof_steps = min(args.steps, 100)
+        prof_steps = min(steps, 100)
         eager_ms = ms_per_step if not use_graph else time_eager(prof_steps)
         m.monta_profile_reset()
         m.monta_profile_enable(True)
@@ -222,22 +191,22 @@ def main():
         S = w.slices
         per_launch = {"pack": None, "regather": None, "pack_regather": None, "combine": ab["combine"],
                       "plan_pack": ab["pack_s"][0] + ab["plan"], "gate": ab.get("gate")}
+        co_scheduled = "pack_regather" in kernels or "plan_pack" in kernels
         if "pack" in kernels:
             npk = round(kernels["pack"]["launches_per_step"])
-            per_launch["pack"] = (sum(ab["pack_s"]) if mode != 1 else ab["pack_s"][0]) / npk
+            per_launch["pack"] = (ab["pack_s"][0] if co_scheduled else sum(ab["pack_s"])) / npk
         if "regather" in kernels:
             nrg = round(kernels["regather"]["launches_per_step"])
-            per_launch["regather"] = (sum(ab["regather_s"]) if mode != 1 else ab["regather_s"][S - 1]) / nrg
+            per_launch["regather"] = (ab["regather_s"][S - 1] if co_scheduled else sum(ab["regather_s"])) / nrg
         if "pack_regather" in kernels:
             tot = sum(ab["pack_s"][j] + ab["regather_s"][j - 1] for j in range(1, S))
             per_launch["pack_regather"] = tot / (S - 1)
         if mirror:
-            S_ = w.slices
             per_launch["unregather"] = ab["unregather_s"][0]
-            per_launch["combine"] = ab["combine_s"][S_ - 1]
-            if S_ > 1:
+            per_launch["combine"] = ab["combine_s"][S - 1]
+            if S > 1:
                 per_launch["unregather_combine"] = sum(ab["unregather_s"][j] + ab["combine_s"][j - 1]
-                                                       for j in range(1, S_)) / (S_ - 1)
+                                                       for j in range(1, S)) / (S - 1)
         movers = [kname for kname in ("pack", "regather", "pack_regather", "combine", "plan_pack", "unregather",
                                       "unregather_combine", "gate") if kname in kernels]
         dom = max(movers, key=lambda kname: kernels[kname]["us_per_step"])
@@ -248,7 +217,7 @@ def main():
         tpath = os.path.join(ROOT, "profiles", "traffic.json")
         if os.path.exists(tpath):
             try:
-                entry = json.load(open(tpath)).get(f"{w.name}/S{w.slices}/mode{mode}", {})
+                entry = json.load(open(tpath)).get(f"{w.name}/S{w.slices}/mode{mode_label(mode)}", {})
                 for kname, v in entry.items():
                     if kname.startswith(dom + "_kernel"):
                         traffic = v["total_bytes"]
@@ -275,6 +244,8 @@ def main():
         for v in kernels.values():
             for kk in list(v):
                 v[kk] = round(v[kk], 3)
+        res["roofline"] = roofline
+        res["kernels"] = kernels
 
     if args.calib_copy_mib > 0:
         nbytes = args.calib_copy_mib << 20
@@ -284,38 +255,137 @@ def main():
             m.monta_copy(dst, src, nbytes, stream)
         torch.cuda.synchronize()
         del src, dst
+    del b
+    return res
 
-    # ---- CPU oracle on this host (a baseline for context, never the target)
-    cpu = None
-    if not args.no_cpu:
-        import oracle
+
+def cpu_baseline(args, w, res):
+    """The CPU oracle on this host, on the whole workload: once on all cores (the OpenMP build of the same
+    source) and once on one thread (the build the parity tests use).  Output arrays are allocated and touched by
+    an untimed first pass, so the timed passes measure the oracle and not the host's page faults."""
+    import oracle
+    import workloads
+    logits, x = res["inputs"]
+    ab = res["ab"]
+    kw = dict(k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm, padded=w.padded)
+
+    def one_pass(reuse):
+        lg = oracle.gate(x, res["w_gate_host"]) if args.gate else logits
+        return oracle.forward(lg, x, reuse=reuse, **kw)
+
+    expert_s, expert_note = 0.0, ""
+    with oracle.all_cores():
+        cores = oracle.threads()
+        ref = one_pass(None)             # untimed: allocates and touches STAGE / FINAL / out
         reps, spent = 0, 0.0
-        budget = 12.0
-        expert_note = ""
-        expert_s = 0.0
-        if args.experts:
-            # the expert layer on a sample of rows of one expert, scaled to all kept rows (the whole layer would take hours)
-            fwd = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm,
-                                 padded=w.padded)
-            lo, hi = oracle.expert_ranges(fwd.plan, w.tp, w.slices)
-            e0 = int(np.argmax(hi - lo))
-            n_rows = int(min(8, hi[e0] - lo[e0]))
-            w_one = workloads.make_expert_weights(w.with_(experts=1))
+        while reps < 50 and spent < 8.0:
             c0 = time.perf_counter()
-            oracle.expert(fwd.final[lo[e0]:lo[e0] + n_rows], w_one, np.array([0], np.int32), np.array([n_rows], np.int32))
-            expert_s = (time.perf_counter() - c0) * ab["R"] / n_rows
-            expert_note = f"; expert layer timed on {n_rows} rows and scaled to {ab['R']} ({expert_s:.0f} s per pass)"
-        while reps < 200 and spent < budget:
-            c0 = time.perf_counter()
-            if args.gate:
-                logits = oracle.gate(x, w_gate_host)
-            oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, renorm=w.renorm,
-                           padded=w.padded)
+            one_pass(ref)
             spent += time.perf_counter() - c0
             reps += 1
-        cpu = {"value": round(w.tokens / (spent / reps + expert_s), 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
-               "sample": f"the whole {w.name} workload, {reps} passes of the single-threaded C oracle, {spent:.1f} s" + expert_note,
-               "effective_GBps": round(ab["total"] / (spent / reps + expert_s) / 1e9, 2)}
+    if args.experts:
+        # the expert layer on a sample of rows of one expert, scaled to all kept rows (the whole layer would take hours)
+        lo, hi = oracle.expert_ranges(ref.plan, w.tp, w.slices)
+        e0 = int(np.argmax(hi - lo))
+        n_rows = int(min(8, hi[e0] - lo[e0]))
+        w_one = workloads.make_expert_weights(w.with_(experts=1))
+        c0 = time.perf_counter()
+        oracle.expert(ref.final[lo[e0]:lo[e0] + n_rows], w_one, np.array([0], np.int32), np.array([n_rows], np.int32))
+        expert_s = (time.perf_counter() - c0) * ab["R"] / n_rows
+        expert_note = f"; expert layer timed on {n_rows} rows on one thread and scaled to {ab['R']} ({expert_s:.0f} s per pass)"
+    reps1, spent1 = 0, 0.0
+    while reps1 < 50 and spent1 < 8.0:
+        c0 = time.perf_counter()
+        one_pass(ref)
+        spent1 += time.perf_counter() - c0
+        reps1 += 1
+    per_pass, per_pass1 = spent / reps + expert_s, spent1 / reps1 + expert_s
+    return {"value": round(w.tokens / per_pass, 1), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"the whole {w.name} workload, {reps} passes of the C oracle on {cores} threads ({spent:.1f} s)" + expert_note,
+            "effective_GBps": round(ab["total"] / per_pass / 1e9, 2),
+            "single_thread": {"value": round(w.tokens / per_pass1, 1), "unit": "tokens/s", "cores": 1,
+                              "sample": f"the whole {w.name} workload, {reps1} passes on one thread ({spent1:.1f} s)",
+                              "effective_GBps": round(ab["total"] / per_pass1 / 1e9, 2)}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="skewed", help="tiny | mixtral | 2x70b | longctx | skewed (default: the largest)")
+    ap.add_argument("--slices", type=int, default=0, help="override the workload's slice count")
+    ap.add_argument("--mode", type=int, default=-1, help="pipeline realisation 0/1/2 (default -1: the library chooses)")
+    ap.add_argument("--graph", type=int, default=0, help="replay the step from a captured HIP graph (1) or launch eagerly (0)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run the plain copy kernel on buffers of this size (profiler byte-counter calibration)")
+    ap.add_argument("--return-path", default="direct", choices=["direct", "mirror"],
+                    help="direct: combine reads the expert output in FINAL layout (the headline path); mirror: the "
+                         "second AllToAll mirrored (unregather + staged combine pipeline), 2R more rows moved")
+    ap.add_argument("--padded", type=int, default=0, help="1: capacity-padded [E][C][H] layout of FINAL (zero-filled padding)")
+    ap.add_argument("--gate", type=int, default=0,
+                    help="1: the step starts one stage earlier, at the gate projection (monta_gate: logits = x * w_gate^T "
+                         "with random-init weights); 0: at the logits, as the headline metric is defined")
+    ap.add_argument("--experts", type=int, default=0,
+                    help="1: a real expert layer (monta_route_dispatch_expert: one H x H linear layer per expert, random-init "
+                         "weights) sits between dispatch and combine instead of identity experts")
+    ap.add_argument("--expert-overlap", type=int, default=0,
+                    help="with --experts 1: 1 = each slice's expert launch overlaps the next slice's movers (second stream)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other named workloads")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build covers one GPU's share of the path; nothing crosses GPUs, so only --gpus 1 is "
+              "supported (virtual EP/TP ranks are buffer partitions on one MI355X).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    import paper_2411_00662_amd as m
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    m.binding.lib()     # no fallback: fails here if the HIP library is not built
+
+    w = workloads.CONFIGS[args.config]
+    if args.slices:
+        w = w.with_(slices=args.slices)
+    if args.padded:
+        w = w.with_(padded=1)
+    m.monta_set_pipeline_mode(args.mode)
+
+    res = measure(args, w, args.steps, args.warmup, full=True)
+    ms_per_step, ab = res["ms_per_step"], res["ab"]
+    tokens_per_s = w.tokens / (ms_per_step * 1e-3)
+    eff_gbps = ab["total"] / (ms_per_step * 1e-3) / 1e9
+
+    # ---- CPU oracle on this host (a baseline for context, never the target)
+    cpu = None if args.no_cpu else cpu_baseline(args, w, res)
+    res.pop("inputs")
+    gc.collect()
+    torch.cuda.empty_cache()
+
+    # ---- the other named workloads, briefly: step time and fraction of the HBM peak (headline path only)
+    others = None
+    plain = not (args.gate or args.experts or args.padded or args.slices or args.return_path != "direct")
+    if not args.no_others and plain:
+        others = {}
+        for name in workloads.CONFIG_ORDER:
+            if name == w.name:
+                continue
+            ow = workloads.CONFIGS[name]
+            r = measure(args, ow, 30, 10, full=False)
+            gb = r["ab"]["total"] / (r["ms_per_step"] * 1e-3) / 1e9
+            others[name] = {"ms_per_step": round(r["ms_per_step"], 5),
+                            "tokens_per_s": round(ow.tokens / (r["ms_per_step"] * 1e-3), 1),
+                            "effective_GBps": round(gb, 1), "pct_of_hbm_peak": round(100 * gb / HBM_PEAK_GBPS, 2),
+                            "kept_rows": r["ab"]["R"], "steps": 30}
+            r.clear()
+            gc.collect()
+            torch.cuda.empty_cache()
 
     line = {
         "metric": "dispatch+combine tokens/s", "value": round(tokens_per_s, 1), "unit": "tokens/s",
@@ -325,12 +395,12 @@ def main():
         "config": {"workload": w.name, "tokens": w.tokens, "hidden": w.hidden, "experts": w.experts,
                    "top_k": w.top_k, "ep": w.ep, "tp": w.tp, "slices": w.slices,
                    "capacity_factor": w.capacity_factor, "kept_rows": ab["R"], "alive_tokens": ab["alive"],
-                   "pipeline_mode": mode, "hip_graph": use_graph, "return_path": args.return_path, "padded": w.padded,
-                   "gate": bool(args.gate), "expert_layer": bool(args.experts), "expert_overlap": int(args.expert_overlap),
-                   "parallelism": "1 GPU, virtual ep/tp"},
+                   "pipeline_mode": mode_label(res["mode"]), "hip_graph": res["use_graph"], "return_path": args.return_path,
+                   "padded": w.padded, "gate": bool(args.gate), "expert_layer": bool(args.experts),
+                   "expert_overlap": int(args.expert_overlap), "parallelism": "1 GPU, virtual ep/tp"},
         "effective_GBps": round(eff_gbps, 1), "pct_of_hbm_peak": round(100 * eff_gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_bytes_per_step": int(ab["total"]),
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": res["roofline"], "cpu_baseline": cpu, "other_configs": others, "kernels": res["kernels"],
     }
     print(json.dumps(line))
 

@@ -30,9 +30,13 @@
  *     calls that share a workspace or a buffer are ordered by the caller (same
  *     stream, or events).  The forms that use the library's side stream
  *     (pipeline mode 0, monta_route_dispatch_expert with overlap = 1) share one
- *     side stream and one set of events per device: two such calls in flight on
- *     one device must come from one thread at a time.  The monta_set_* switches
- *     are process-wide.
+ *     side stream and one set of events per device; such a call holds a per-device
+ *     lock while it enqueues, so calls from several threads are safe and run one
+ *     after the other on the side stream.  The monta_set_* switches are
+ *     process-wide; every entry point reads them once, when it is called, and
+ *     uses that snapshot for all of its work, so a switch changed by another
+ *     thread takes effect at the next call, never in the middle of one.
+ *     monta_shutdown() releases the side streams and events.
  *   - Limits: 1 <= top_k <= experts <= 256, top_k <= 32, experts % ep == 0,
  *     tokens % (slices * tp) == 0, tokens * top_k < 2^31,
  *     hidden * sizeof(element) % 16 == 0; activation base pointers 16-byte
@@ -249,7 +253,9 @@ int monta_unregather_combine(const monta_cfg *cfg, const void *y, void *y_stage,
  *   1  one stream, co-scheduled grids: launch j does regather(j-1) and pack(j) in
  *      disjoint workgroups of one grid (S+1 launches, no events);
  *   2  one stream, strictly serial pack(0), regather(0), pack(1), ...
- * Returns MONTA_ERR_INVALID for other values.  Process-wide; default 1. */
+ *  -1  (default) chosen per call from what one slice moves: 1 while a slice's copies are
+ *      short enough for the launch boundaries to matter (up to 256 MiB per slice), 2 above.
+ * Returns MONTA_ERR_INVALID for other values.  Process-wide. */
 int monta_set_pipeline_mode(int mode);
 int monta_get_pipeline_mode(void);
 
@@ -347,6 +353,11 @@ int monta_plan_strategy(const monta_plan_in *in, monta_plan_out *out);
 const char *monta_strerror(int code);
 /* The hipError_t (as int) behind the calling thread's last MONTA_ERR_HIP, 0 if none. */
 int monta_last_hip_error(void);
+
+/* Waits for the library's side streams, then destroys them, their events and any pending profiling
+ * events, on every device that used them.  No other call of the library may be in flight.  The library
+ * works again afterwards (the resources are created on demand). */
+int monta_shutdown(void);
 
 #ifdef __cplusplus
 }

@@ -19,26 +19,51 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "monta_oracle.c")
 _LIB = os.path.join(_HERE, "libmonta_oracle.so")
-_lib = None
+_LIB_OMP = os.path.join(_HERE, "libmonta_oracle_omp.so")     # same source with -fopenmp: the all-cores timing build
+_libs = {}
+_use_omp = False
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc.  -O1 and no fast-math: keep it plain and IEEE."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fno-fast-math",
-               "-ffp-contract=off", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
-        subprocess.run(cmd, check=True)
+    """Compile the oracle with gcc, twice: the plain single-threaded build (the parity reference) and the same
+    source with -fopenmp (the all-cores CPU baseline).  -O1 and no fast-math: keep it plain and IEEE."""
+    for lib, extra in ((_LIB, []), (_LIB_OMP, ["-fopenmp"])):
+        if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+            cmd = ["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fno-fast-math",
+                   "-ffp-contract=off", "-Wall", "-Wextra", *extra, "-o", lib, _SRC, "-lm"]
+            subprocess.run(cmd, check=True)
     return _LIB
 
 
+class all_cores:
+    """``with oracle.all_cores():`` routes the calls inside to the OpenMP build (timing only)."""
+
+    def __enter__(self):
+        global _use_omp
+        self._old = _use_omp
+        _use_omp = True
+        return self
+
+    def __exit__(self, *exc):
+        global _use_omp
+        _use_omp = self._old
+
+
+def threads() -> int:
+    """Threads the current build's loops run on (1 for the plain build)."""
+    return int(_load().monta_oracle_threads())
+
+
 def _load():
-    global _lib
-    if _lib is None:
+    path = _LIB_OMP if _use_omp else _LIB
+    lib = _libs.get(path)
+    if lib is None:
         build()
-        _lib = ctypes.CDLL(_LIB)
-        _lib.monta_oracle_capacity.restype = ctypes.c_int64
-        _lib.monta_oracle_capacity.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double]
-    return _lib
+        lib = ctypes.CDLL(path)
+        lib.monta_oracle_capacity.restype = ctypes.c_int64
+        lib.monta_oracle_capacity.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double]
+        _libs[path] = lib
+    return lib
 
 
 def _p(a: np.ndarray):
@@ -172,8 +197,8 @@ def pad(final: np.ndarray, pl: Plan) -> np.ndarray:
     return final
 
 
-def combine(y: np.ndarray, gates: np.ndarray, pos_final: np.ndarray) -> np.ndarray:
-    """y [R,H] float32 or uint16(bf16) -> out [T,H] of the same type."""
+def combine(y: np.ndarray, gates: np.ndarray, pos_final: np.ndarray, out: np.ndarray | None = None) -> np.ndarray:
+    """y [R,H] float32 or uint16(bf16) -> out [T,H] of the same type (a preallocated `out` is filled in place)."""
     y = np.ascontiguousarray(y)
     gates = np.ascontiguousarray(gates, dtype=np.float32)
     pos_final = np.ascontiguousarray(pos_final, dtype=np.int32)
@@ -187,7 +212,9 @@ def combine(y: np.ndarray, gates: np.ndarray, pos_final: np.ndarray) -> np.ndarr
         raise ValueError("oracle combine: y must be float32 or uint16 (bf16 bits)")
     if pos_final.max(initial=-1) >= y.shape[0]:
         raise ValueError("oracle combine: position outside y")
-    out = np.empty((T, H), y.dtype)
+    if out is None:
+        out = np.empty((T, H), y.dtype)
+    assert out.flags.c_contiguous and out.dtype == y.dtype and out.shape == (T, H)
     rc = _load().monta_oracle_combine(ctypes.c_int64(T), H, k, dtype, _p(y), _p(gates), _p(pos_final), _p(out))
     _check(rc, "combine")
     return out
@@ -289,14 +316,15 @@ class Result:
     out: np.ndarray
 
 
-def forward(logits, x, *, k, ep, tp, S, cf, renorm=1, padded=0, fill=0) -> Result:
-    """The whole path with identity experts (expert output = FINAL)."""
+def forward(logits, x, *, k, ep, tp, S, cf, renorm=1, padded=0, fill=0, reuse: Result | None = None) -> Result:
+    """The whole path with identity experts (expert output = FINAL).  `reuse`: a result of the same problem whose
+    STAGE / FINAL / out arrays are written again instead of allocating fresh ones (for timing without page faults)."""
     E = logits.shape[1]
     idx, gates = route(logits, k, renorm)
     pl = plan(idx, E, ep, tp, S, cf, padded)
-    stage = pack(x, pl, tp, S)
-    final = regather(stage, pl, tp, S, fill=fill)
+    stage = pack(x, pl, tp, S, stage=None if reuse is None else reuse.stage)
+    final = regather(stage, pl, tp, S, final=None if reuse is None else reuse.final, fill=fill)
     if padded:
         pad(final, pl)
-    out = combine(final, gates, pl.pos_final)
+    out = combine(final, gates, pl.pos_final, out=None if reuse is None else reuse.out)
     return Result(idx, gates, pl, stage, final, out)

@@ -1,6 +1,12 @@
 /*
- * monta_oracle.c -- plain, slow, single-threaded CPU reference of the MoE token
- * dispatch / combine path of MoNTA (arxiv 2411.00662).
+ * monta_oracle.c -- plain, slow CPU reference of the MoE token dispatch / combine
+ * path of MoNTA (arxiv 2411.00662).  Built without OpenMP it is single-threaded:
+ * that build is the parity reference.  A second build with -fopenmp runs the same
+ * loops with the independent outer iterations (tokens, rows, blocks) of route,
+ * pack, regather and combine dealt to all host cores; it exists only to time the
+ * CPU baseline on every core, computes exactly the same bytes (no iteration reads
+ * what another writes) and is checked against the first build by a test.  The plan
+ * stays serial in both.
  *
  * THIS IS TEST INFRASTRUCTURE.  It exists so that the HIP path can be checked
  * against something that is obviously the definition.  Only tests, the smoke
@@ -41,6 +47,23 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#define ORACLE_PARALLEL_FOR _Pragma("omp parallel for schedule(static)")
+#else
+#define ORACLE_PARALLEL_FOR
+#endif
+
+/* threads the loops above run on: 1 in the plain build */
+int monta_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 #define ORACLE_OK 0
 #define ORACLE_BAD_ARG (-1)
 #define ORACLE_NOMEM (-2)
@@ -59,10 +82,11 @@ int monta_oracle_route(int64_t T, int E, int k, int renorm, const float *logits,
 {
     if (T < 0 || E < 1 || k < 1 || k > E || !logits || !topk_idx || !gates)
         return ORACLE_BAD_ARG;
-    char *taken = (char *)malloc((size_t)E);
-    double *w = (double *)malloc(sizeof(double) * (size_t)k);
-    if (!taken || !w) { free(taken); free(w); return ORACLE_NOMEM; }
+    if (E > 4096) return ORACLE_BAD_ARG;       /* the per-token scratch below lives on the stack */
+    ORACLE_PARALLEL_FOR
     for (int64_t t = 0; t < T; ++t) {
+        char taken[4096];
+        double w[4096];
         const float *l = logits + t * E;
         memset(taken, 0, (size_t)E);
         for (int j = 0; j < k; ++j) {
@@ -84,8 +108,6 @@ int monta_oracle_route(int64_t T, int E, int k, int renorm, const float *logits,
             for (int e = 0; e < E; ++e) denom += exp((double)l[e] - top);
         for (int j = 0; j < k; ++j) gates[t * k + j] = (float)(w[j] / denom);
     }
-    free(taken);
-    free(w);
     return ORACLE_OK;
 }
 
@@ -248,6 +270,7 @@ int monta_oracle_pack(int64_t T, int k, int tp, int S, int64_t row_bytes, const 
     if (T % U != 0) return ORACLE_BAD_ARG;
     for (int64_t u = 0; u < U; ++u) {
         if (slice >= 0 && u / tp != slice) continue;
+        ORACLE_PARALLEL_FOR
         for (int64_t t = u * Tu; t < (u + 1) * Tu; ++t)
             for (int j = 0; j < k; ++j) {
                 int32_t p = pos_stage[t * k + j];
@@ -281,6 +304,7 @@ int monta_oracle_regather(int tp, int S, int E, int64_t row_bytes, const int32_t
     const int64_t U = (int64_t)S * tp;
     for (int64_t u = 0; u < U; ++u) {
         if (slice >= 0 && u / tp != slice) continue;
+        ORACLE_PARALLEL_FOR
         for (int e = 0; e < E; ++e)
             memcpy((char *)final_ + (int64_t)unit_base[u * E + e] * row_bytes,
                    (const char *)stage + (int64_t)stage_off[u * E + e] * row_bytes,
@@ -329,6 +353,7 @@ int monta_oracle_combine(int64_t T, int H, int k, int dtype, const void *y,
                          const float *gates, const int32_t *pos_final, void *out)
 {
     if (T < 0 || H < 1 || k < 1 || (dtype != 0 && dtype != 1)) return ORACLE_BAD_ARG;
+    ORACLE_PARALLEL_FOR
     for (int64_t t = 0; t < T; ++t)
         for (int h = 0; h < H; ++h) {
             double acc = 0.0;

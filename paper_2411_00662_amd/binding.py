@@ -73,7 +73,7 @@ EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "m
            "monta_unregather_combine", "monta_allgather", "monta_set_pipeline_mode",
            "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
            "monta_profile_read", "monta_plan_chunk_times", "monta_plan_strategy", "monta_strerror",
-           "monta_last_hip_error"]
+           "monta_last_hip_error", "monta_shutdown"]
 
 _lib = None
 
@@ -118,6 +118,7 @@ def lib() -> ctypes.CDLL:
         L.monta_strerror.argtypes = [i32]
         L.monta_strerror.restype = ctypes.c_char_p
         L.monta_last_hip_error.argtypes = []
+        L.monta_shutdown.argtypes = []
         for name in EXPORTS:
             if name != "monta_strerror":
                 getattr(L, name).restype = ctypes.c_int
@@ -131,6 +132,10 @@ def monta_strerror(code: int) -> str:
 
 def monta_last_hip_error() -> int:
     return int(lib().monta_last_hip_error())
+
+
+def monta_shutdown():
+    _check(lib().monta_shutdown(), "monta_shutdown")
 
 
 def _check(code: int, what: str):

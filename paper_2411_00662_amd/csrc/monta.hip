@@ -24,9 +24,17 @@ using namespace monta;
 constexpr int kCombineWideVpr = 2 * kMoverThreads;
 
 thread_local int g_last_hip = 0;
-std::atomic<int> g_pipeline_mode{1};
+std::atomic<int> g_pipeline_mode{-1};  // -1: chosen from the bytes one slice moves
 std::atomic<int> g_plan_mode{-1};      // -1: per-workgroup rebuild when the histogram table is small; 0: always ticketed scan
 std::atomic<int> g_cache_policy{-1};   // -1: chosen from the working-set size
+
+// The process-wide switches as one entry point saw them when it was called: every decision of that call, and of
+// the internal steps it is made of, uses this snapshot, so a switch flipped by another thread takes effect at
+// the next call and never in the middle of one.
+struct Modes {
+    int pipeline, plan, cache;
+};
+Modes snapshot_modes() { return {g_pipeline_mode.load(), g_plan_mode.load(), g_cache_policy.load()}; }
 
 #define HIP_TRY(expr)                          \
     do {                                       \
@@ -51,6 +59,7 @@ constexpr size_t kRouteLdsBudget = 120 * 1024;
 
 struct Geometry {
     Shape s;
+    Modes modes;
     int64_t max_rows;
     int64_t row_bytes;
     size_t route_lds;
@@ -77,6 +86,7 @@ size_t route_lds_bytes(int TB, int E, int k)
 int validate(const monta_cfg *c, Geometry *g)
 {
     if (!c) return MONTA_ERR_NULL;
+    g->modes = snapshot_modes();
     if (c->tokens < 1 || c->hidden < 1 || c->experts < 1 || c->top_k < 1 || c->ep < 1 || c->tp < 1 || c->slices < 1)
         return MONTA_ERR_INVALID;
     if (c->dtype != MONTA_FP32 && c->dtype != MONTA_BF16) return MONTA_ERR_INVALID;
@@ -118,7 +128,7 @@ int validate(const monta_cfg *c, Geometry *g)
     if (nb * s.E > 0x7fffffffLL) return MONTA_ERR_UNSUPPORTED;
     s.num_blocks = (int32_t)nb;
     // the per-workgroup rebuild of the scans reads num_blocks*E counters in every workgroup
-    s.fast_plan = (g_plan_mode.load() != 0 && nb * s.E <= 65536) ? 1 : 0;
+    s.fast_plan = (g->modes.plan != 0 && nb * s.E <= 65536) ? 1 : 0;
     g->route_lds = route_lds_bytes(TB, s.E, s.k);
     g->plan_threads = TB < kWave ? kWave : TB;
     // lanes per token in the route kernel: each lane should still scan at least 8 experts
@@ -134,7 +144,7 @@ int validate(const monta_cfg *c, Geometry *g)
     {
         // Measured on MI355X (256 MB memory-side cache): a producer's cacheable stores pay when the
         // consumer kernel reads them back soon; beyond the cache everything but the pack stores streams.
-        const int pol = g_cache_policy.load();
+        const int pol = g->modes.cache;
         const int64_t touched = (2 * c->tokens + 2 * g->max_rows) * row;   // x + out + STAGE + FINAL
         if (pol >= 0) s.cache = pol;
         else if (touched <= (384ll << 20)) s.cache = NT_REG_LD | NT_COMB_ST;
@@ -303,6 +313,7 @@ int prof_drain()
 // ------------------------------------------------- side stream for mode 0
 
 struct DevState {
+    std::mutex mu;              // held while a call enqueues work that uses the side stream or the events
     hipStream_t side = nullptr;
     std::vector<hipEvent_t> ev;
     hipEvent_t done = nullptr;
@@ -331,6 +342,7 @@ int dev_state(int nslices, DevState **out)
 // ------------------------------------------------------------ launch shapes
 
 constexpr int kMaxMoverGrid = 1 << 16;
+constexpr int64_t kSerialSliceBytes = 256ll << 20;   // above this a slice's pack and regather run as two kernels
 
 int mover_grid(const Shape &s, int64_t rows)
 {
@@ -598,6 +610,101 @@ int launch_expert_layer(const monta_cfg *cfg, const Geometry &g, const void *x_f
     return MONTA_OK;
 }
 
+// The pipeline realisation one call uses: the caller's choice, or (-1) picked from what one slice moves.
+// Measured on MI355X: a co-scheduled launch (pack of slice j and regather of slice j-1 in one grid) saves a
+// launch boundary per slice, which decides it while a slice's copies take a few tens of microseconds; once they
+// take hundreds, two plain kernels run faster than the mixed grid (the regather alone reaches 6.6-7.0 TB/s, the
+// mixed grid 6.2-6.7) and the boundary no longer matters.
+int effective_pipeline_mode(const Geometry &g)
+{
+    if (g.modes.pipeline >= 0) return g.modes.pipeline;
+    const int64_t slice_bytes = slice_rows_bound(g, 1) * g.row_bytes;      // rows one slice may put into STAGE
+    return slice_bytes > kSerialSliceBytes ? 2 : 1;
+}
+
+int route_impl(const Geometry &g, const float *logits, int32_t *topk_idx, float *gates, void *ws, hipStream_t st)
+{
+    const Shape &s = g.s;
+    PlanPtrs p = plan_ptrs(g, ws);
+    if (int rc = launch_route(g, p, logits, topk_idx, gates, st)) return rc;
+    ProfScope ps(MONTA_K_POSITIONS, st);
+    if (s.fast_plan)
+        hipLaunchKernelGGL(plan_positions_kernel, dim3(s.num_blocks), dim3(g.plan_threads), 0, st, topk_idx, p, s);
+    else
+        hipLaunchKernelGGL(positions_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, topk_idx, p, s);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+int dispatch_regather_impl(const Geometry &g, const void *x, void *stage, void *final_, const void *ws, hipStream_t st)
+{
+    int rc = MONTA_OK;
+    const PlanPtrs p = plan_ptrs(g, ws);
+    const int S = g.s.S;
+    const int mode = effective_pipeline_mode(g);
+    if (mode == 2) {
+        for (int j = 0; j < S; ++j) {
+            if ((rc = launch_pack(g, p, x, stage, j, st))) return rc;
+            if ((rc = launch_regather(g, p, stage, final_, j, st))) return rc;
+        }
+        return MONTA_OK;
+    }
+    if (mode == 1) {
+        if ((rc = launch_pack(g, p, x, stage, 0, st))) return rc;
+        for (int j = 1; j < S; ++j)
+            if ((rc = launch_pack_regather(g, p, x, stage, final_, j, st))) return rc;
+        return launch_regather(g, p, stage, final_, S - 1, st);
+    }
+    // mode 0: packs on the caller's stream, regathers on the side stream, one event per slice.  The side stream
+    // and its events are shared by every caller on this device: the whole enqueue holds the device's lock, so
+    // that each wait pairs with the record made just before it (a wait refers to the event's latest record at
+    // the time the wait is enqueued; what another call records later does not change it).
+    DevState *d = nullptr;
+    if ((rc = dev_state(S, &d))) return rc;
+    std::lock_guard<std::mutex> lk(d->mu);
+    for (int j = 0; j < S; ++j) {
+        if ((rc = launch_pack(g, p, x, stage, j, st))) return rc;
+        HIP_TRY(hipEventRecord(d->ev[j], st));
+        HIP_TRY(hipStreamWaitEvent(d->side, d->ev[j], 0));
+        prof_break_chain(d->side);
+        if ((rc = launch_regather(g, p, stage, final_, j, d->side))) return rc;
+    }
+    HIP_TRY(hipEventRecord(d->done, d->side));
+    HIP_TRY(hipStreamWaitEvent(st, d->done, 0));
+    prof_break_chain(st);
+    return MONTA_OK;
+}
+
+int route_dispatch_regather_impl(const Geometry &g, const float *logits, const void *x, int32_t *topk_idx, float *gates,
+                                 void *stage, void *final_, void *ws, hipStream_t st)
+{
+    int rc = MONTA_OK;
+    const Shape &s = g.s;
+    const int rows_per_wg = kMoverThreads / s.lpr;
+    // The overlapped form needs a histogram table small enough to rebuild in every pack workgroup and
+    // token groups that never straddle two route workgroups.
+    const bool overlap = effective_pipeline_mode(g) == 1 && s.fast_plan && (int64_t)s.num_blocks * s.E <= 2048 &&
+                         s.Tu % s.TB == 0 && rows_per_wg <= s.TB && kMoverThreads >= s.TB;
+    if (!overlap) {
+        if ((rc = route_impl(g, logits, topk_idx, gates, ws, st))) return rc;
+        return dispatch_regather_impl(g, x, stage, final_, ws, st);
+    }
+    PlanPtrs p = plan_ptrs(g, ws);
+    if ((rc = launch_route(g, p, logits, topk_idx, gates, st))) return rc;
+    {
+        const int per_slice = s.tp * s.Tu;
+        const int n_pack = (per_slice + rows_per_wg - 1) / rows_per_wg;     // one token group per workgroup, no striding
+        ProfScope ps(MONTA_K_PLAN_PACK, st);
+        hipLaunchKernelGGL(plan_pack_kernel, dim3(s.num_blocks + n_pack), dim3(kMoverThreads), 0, st, topk_idx,
+                           static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), p, s, 0, per_slice,
+                           s.num_blocks);
+        HIP_TRY(hipGetLastError());
+    }
+    for (int j = 1; j < s.S; ++j)
+        if ((rc = launch_pack_regather(g, p, x, stage, final_, j, st))) return rc;
+    return launch_regather(g, p, stage, final_, s.S - 1, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -707,7 +814,7 @@ int monta_route_dispatch_expert(const monta_cfg *cfg, const float *logits, const
     if (overlap != 0 && overlap != 1) return MONTA_ERR_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (!overlap) {
-        if ((rc = monta_route_dispatch_regather(cfg, logits, x, topk_idx, gates, stage, final_, ws, stream))) return rc;
+        if ((rc = route_dispatch_regather_impl(g, logits, x, topk_idx, gates, stage, final_, ws, st))) return rc;
         return launch_expert_layer(cfg, g, final_, w_exp, out_features, y, ws, -1, st);
     }
     // Overlapped: the slice pipeline of pipeline mode 1 on the caller's stream, an event behind the kernel that
@@ -716,7 +823,8 @@ int monta_route_dispatch_expert(const monta_cfg *cfg, const float *logits, const
     const int S = g.s.S;
     DevState *d = nullptr;
     if ((rc = dev_state(S, &d))) return rc;
-    if ((rc = monta_route(cfg, logits, topk_idx, gates, ws, stream))) return rc;
+    std::lock_guard<std::mutex> lk(d->mu);      // the side stream and its events are shared per device
+    if ((rc = route_impl(g, logits, topk_idx, gates, ws, st))) return rc;
     const PlanPtrs p = plan_ptrs(g, ws);
     if ((rc = launch_pack(g, p, x, stage, 0, st))) return rc;
     for (int j = 0; j < S; ++j) {
@@ -740,19 +848,7 @@ int monta_route(const monta_cfg *cfg, const float *logits, int32_t *topk_idx, fl
     int rc = validate(cfg, &g);
     if (rc) return rc;
     if ((rc = check_route_ptrs(logits, topk_idx, gates, ws))) return rc;
-    const Shape &s = g.s;
-    PlanPtrs p = plan_ptrs(g, ws);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if ((rc = launch_route(g, p, logits, topk_idx, gates, st))) return rc;
-    {
-        ProfScope ps(MONTA_K_POSITIONS, st);
-        if (s.fast_plan)
-            hipLaunchKernelGGL(plan_positions_kernel, dim3(s.num_blocks), dim3(g.plan_threads), 0, st, topk_idx, p, s);
-        else
-            hipLaunchKernelGGL(positions_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, topk_idx, p, s);
-        HIP_TRY(hipGetLastError());
-    }
-    return MONTA_OK;
+    return route_impl(g, logits, topk_idx, gates, ws, static_cast<hipStream_t>(stream));
 }
 
 int monta_route_dispatch_regather(const monta_cfg *cfg, const float *logits, const void *x, int32_t *topk_idx,
@@ -765,31 +861,7 @@ int monta_route_dispatch_regather(const monta_cfg *cfg, const float *logits, con
     if ((rc = check_act_ptrs(x, stage))) return rc;
     if ((rc = check_act_ptrs(stage, final_))) return rc;
     if (stage == final_) return MONTA_ERR_INVALID;
-    const Shape &s = g.s;
-    const int rows_per_wg = kMoverThreads / s.lpr;
-    // The overlapped form needs a histogram table small enough to rebuild in every pack workgroup and
-    // token groups that never straddle two route workgroups.
-    const bool overlap = g_pipeline_mode.load() == 1 && s.fast_plan && (int64_t)s.num_blocks * s.E <= 2048 &&
-                         s.Tu % s.TB == 0 && rows_per_wg <= s.TB && kMoverThreads >= s.TB;
-    if (!overlap) {
-        if ((rc = monta_route(cfg, logits, topk_idx, gates, ws, stream))) return rc;
-        return monta_dispatch_regather(cfg, x, stage, final_, ws, stream);
-    }
-    PlanPtrs p = plan_ptrs(g, ws);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if ((rc = launch_route(g, p, logits, topk_idx, gates, st))) return rc;
-    {
-        const int per_slice = s.tp * s.Tu;
-        const int n_pack = (per_slice + rows_per_wg - 1) / rows_per_wg;     // one token group per workgroup, no striding
-        ProfScope ps(MONTA_K_PLAN_PACK, st);
-        hipLaunchKernelGGL(plan_pack_kernel, dim3(s.num_blocks + n_pack), dim3(kMoverThreads), 0, st, topk_idx,
-                           static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), p, s, 0, per_slice,
-                           s.num_blocks);
-        HIP_TRY(hipGetLastError());
-    }
-    for (int j = 1; j < s.S; ++j)
-        if ((rc = launch_pack_regather(g, p, x, stage, final_, j, st))) return rc;
-    return launch_regather(g, p, stage, final_, s.S - 1, st);
+    return route_dispatch_regather_impl(g, logits, x, topk_idx, gates, stage, final_, ws, static_cast<hipStream_t>(stream));
 }
 
 int monta_dispatch(const monta_cfg *cfg, const void *x, void *stage, const void *ws, int slice, void *stream)
@@ -825,37 +897,7 @@ int monta_dispatch_regather(const monta_cfg *cfg, const void *x, void *stage, vo
     if ((rc = check_act_ptrs(stage, final_))) return rc;
     if (stage == final_) return MONTA_ERR_INVALID;
     if ((rc = check_ws(ws))) return rc;
-    const PlanPtrs p = plan_ptrs(g, ws);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int S = g.s.S;
-    const int mode = g_pipeline_mode.load();
-    if (mode == 2) {
-        for (int j = 0; j < S; ++j) {
-            if ((rc = launch_pack(g, p, x, stage, j, st))) return rc;
-            if ((rc = launch_regather(g, p, stage, final_, j, st))) return rc;
-        }
-        return MONTA_OK;
-    }
-    if (mode == 1) {
-        if ((rc = launch_pack(g, p, x, stage, 0, st))) return rc;
-        for (int j = 1; j < S; ++j)
-            if ((rc = launch_pack_regather(g, p, x, stage, final_, j, st))) return rc;
-        return launch_regather(g, p, stage, final_, S - 1, st);
-    }
-    // mode 0: packs on the caller's stream, regathers on the side stream, one event per slice
-    DevState *d = nullptr;
-    if ((rc = dev_state(S, &d))) return rc;
-    for (int j = 0; j < S; ++j) {
-        if ((rc = launch_pack(g, p, x, stage, j, st))) return rc;
-        HIP_TRY(hipEventRecord(d->ev[j], st));
-        HIP_TRY(hipStreamWaitEvent(d->side, d->ev[j], 0));
-        prof_break_chain(d->side);
-        if ((rc = launch_regather(g, p, stage, final_, j, d->side))) return rc;
-    }
-    HIP_TRY(hipEventRecord(d->done, d->side));
-    HIP_TRY(hipStreamWaitEvent(st, d->done, 0));
-    prof_break_chain(st);
-    return MONTA_OK;
+    return dispatch_regather_impl(g, x, stage, final_, ws, static_cast<hipStream_t>(stream));
 }
 
 int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void *out, const void *ws, void *stream)
@@ -944,7 +986,7 @@ int launch_unregather_combine(const Geometry &g, const PlanPtrs &p, int dtype, c
 {
     Shape s = g.s;
     // the rows fetched back are read exactly once by the staged combine: stream them unless the caller set a policy
-    if (g_cache_policy.load() < 0) s.cache |= NT_COMB_LD;
+    if (g.modes.cache < 0) s.cache |= NT_COMB_LD;
     const int n_unreg = u0 < u1 ? regather_grid(s, slice_rows_bound(g, (u1 - u0) / s.tp)) : 0;
     const int n_comb = nt > 0 ? mover_grid(s, nt) : 0;
     if (n_unreg + n_comb == 0) return MONTA_OK;
@@ -1015,7 +1057,7 @@ int monta_unregather_combine(const monta_cfg *cfg, const void *y, void *y_stage,
 
 int monta_set_pipeline_mode(int mode)
 {
-    if (mode < 0 || mode > 2) return MONTA_ERR_INVALID;
+    if (mode < -1 || mode > 2) return MONTA_ERR_INVALID;
     g_pipeline_mode.store(mode);
     return MONTA_OK;
 }
@@ -1100,5 +1142,32 @@ const char *monta_strerror(int code)
 }
 
 int monta_last_hip_error(void) { return g_last_hip; }
+
+int monta_shutdown(void)
+{
+    int rc = prof_drain();
+    std::lock_guard<std::mutex> lk(g_dev_mu);
+    int cur = 0;
+    HIP_TRY(hipGetDevice(&cur));
+    for (int dev = 0; dev < 64; ++dev) {
+        DevState &d = g_dev[dev];
+        if (!d.side && !d.done && d.ev.empty()) continue;
+        std::lock_guard<std::mutex> dl(d.mu);
+        HIP_TRY(hipSetDevice(dev));
+        if (d.side) {
+            HIP_TRY(hipStreamSynchronize(d.side));
+            HIP_TRY(hipStreamDestroy(d.side));
+            d.side = nullptr;
+        }
+        for (hipEvent_t e : d.ev) HIP_TRY(hipEventDestroy(e));
+        d.ev.clear();
+        if (d.done) {
+            HIP_TRY(hipEventDestroy(d.done));
+            d.done = nullptr;
+        }
+    }
+    HIP_TRY(hipSetDevice(cur));
+    return rc;
+}
 
 }  // extern "C"

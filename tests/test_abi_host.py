@@ -141,13 +141,14 @@ def test_null_and_misaligned_pointers_fail_before_any_gpu_work():
 
 
 def test_pipeline_mode_and_strerror():
-    assert m.monta_get_pipeline_mode() in (0, 1, 2)
+    assert m.monta_get_pipeline_mode() == -1        # default: chosen per call from the slice size
     old = m.monta_get_pipeline_mode()
-    for mode in (0, 1, 2):
+    for mode in (-1, 0, 1, 2):
         m.monta_set_pipeline_mode(mode)
         assert m.monta_get_pipeline_mode() == mode
-    with pytest.raises(m.MontaError):
-        m.monta_set_pipeline_mode(3)
+    for bad_mode in (3, -2):
+        with pytest.raises(m.MontaError):
+            m.monta_set_pipeline_mode(bad_mode)
     m.monta_set_pipeline_mode(old)
     for code in (0, -1, -2, -3, -4, -5, -77):
         assert isinstance(m.monta_strerror(code), str) and m.monta_strerror(code)

@@ -69,6 +69,7 @@ def run_gpu(m, w, logits, x, mode=1, how="pipeline", canary=0xA5, repeats=1, pla
             raise ValueError(how)
         m.monta_combine(cfg, b.final, b.gates, b.out, b.ws)
     torch.cuda.synchronize()
+    m.monta_set_pipeline_mode(-1)
     m.monta_set_plan_mode(-1)
     m.monta_set_cache_policy(-1)
     tabs = m.read_tables(cfg, b.ws)
@@ -185,7 +186,7 @@ def test_named_8k_workloads(m, name, seed):
         got = run_gpu(m, w, logits, x, mode=1, cache=cache, how="fused_call" if cache in (0, 21) else "pipeline")
         check_against_oracle(w, logits, x, got, ref)
     _say(f"{name} seed={seed} fused call, twice")
-    got = run_gpu(m, w, logits, x, mode=1, how="fused_call", repeats=2)
+    got = run_gpu(m, w, logits, x, mode=-1, how="fused_call", repeats=2)      # the calls and the mode bench.py times
     check_against_oracle(w, logits, x, got, ref)
     if name == "2x70b":
         # top-1, gate 1.0: exact round trip (as values: 0 + 1*(-0) is +0, so a -0 input comes back as +0)
@@ -210,9 +211,9 @@ def test_longctx_slice_sweep(m):
         else:
             ref = oracle.Result(idx, gates, pl, stage, ref1.final, ref1.out)    # FINAL and out do not depend on S
             np.testing.assert_array_equal(pl.pos_final, ref1.plan.pos_final)
-        for mode in ((0, 1) if S in (1, 4) else (1,)):
+        for mode in ((0, 1, -1) if S in (1, 4) else (1, -1)):
             _say(f"longctx S={S} mode={mode} gpu")
-            got = run_gpu(m, w, logits, x, mode=mode, how="fused_call" if mode == 1 else "pipeline")
+            got = run_gpu(m, w, logits, x, mode=mode, how="fused_call" if mode in (1, -1) else "pipeline")
             check_against_oracle(w, logits, x, got, ref)
         del stage
 
@@ -223,8 +224,8 @@ def test_skewed_full_size(m):
     _say("skewed oracle")
     ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor)
     assert ref.plan.R == 233178 and ref.plan.alive == 63030
-    _say("skewed gpu mode 1, the calls bench.py times")
-    got = run_gpu(m, w, logits, x, mode=1, how="fused_call")
+    _say("skewed gpu, default mode, the calls bench.py times")
+    got = run_gpu(m, w, logits, x, mode=-1, how="fused_call")
     # full buffers are 7 GiB each on the host: compare the live part, then the canary on a sample of the tail
     R = ref.plan.R
     for name in ("stage_full", "final_full"):

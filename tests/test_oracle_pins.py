@@ -792,3 +792,26 @@ def test_named_workloads_route_and_plan_at_full_size(name):
     if name == "skewed":
         assert pl.alive == 63030 and int(counts.min()) == 146
         assert list(pl.send_rows.sum(0)) == [81920, 78017, 38625, 16924, 8621, 4700, 2721, 1650]
+
+
+# ------------------------------------------------------------ the all-cores timing build
+
+@pytest.mark.parametrize("dtype,cf,padded", [(BF16, 0.6, 0), (FP32, 0.0, 0), (BF16, 1.25, 1)])
+def test_openmp_build_gives_the_same_bytes_as_the_plain_build(dtype, cf, padded):
+    """The -fopenmp build of the same source (used only to time the CPU baseline on every core) deals
+    independent iterations to threads: every array it produces must equal the single-threaded build's."""
+    w = Workload("omp", 1536, 264, dtype, 12, 3, 4, 2, 3, cf, zipf_s=0.9, padded=padded)
+    logits, x = workloads.make_inputs(w, seed=11)
+    kw = dict(k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, padded=padded)
+    assert oracle.threads() == 1
+    a = oracle.forward(logits, x, **kw)
+    with oracle.all_cores():
+        assert oracle.threads() >= 1
+        b = oracle.forward(logits, x, **kw)
+        c = oracle.forward(logits, x, reuse=b, **kw)        # written again in place: the timing loop's form
+    assert oracle.threads() == 1
+    for r in (b, c):
+        for f in ("topk_idx", "gates", "stage", "final", "out"):
+            assert np.array_equal(getattr(a, f).view(np.uint8), getattr(r, f).view(np.uint8)), f
+        for f in ("counts", "kept", "offsets", "pos_final", "pos_stage", "n", "stage_off", "unit_base", "send_rows"):
+            assert np.array_equal(getattr(a.plan, f), getattr(r.plan, f)), f
