@@ -72,7 +72,8 @@ enum monta_status {
     MONTA_ERR_UNSUPPORTED = -2, /* valid in principle, outside this library's limits        */
     MONTA_ERR_NULL = -3,        /* a required pointer is NULL                               */
     MONTA_ERR_HIP = -4,         /* a HIP runtime call failed; see monta_last_hip_error()    */
-    MONTA_ERR_ALIGN = -5        /* a pointer is not aligned as required                     */
+    MONTA_ERR_ALIGN = -5,       /* a pointer is not aligned as required                     */
+    MONTA_ERR_TOO_LARGE = -6    /* monta_route_dispatch_combine_static: the plan tables exceed the static array */
 };
 
 /* The problem statement: tokens, hidden, experts, top-k, ep, tp, slices, capacity. */
@@ -227,6 +228,21 @@ int monta_route_dispatch_regather(const monta_cfg *cfg, const float *logits, con
  * layout (FINAL itself under identity experts), out [T][H]. */
 int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void *out, const void *ws,
                   void *stream);
+
+/* For callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The whole step with identity experts --
+ * monta_route_dispatch_regather followed by monta_combine(y = final_) -- with the plan tables kept in a
+ * file-scope device array of the library (16 MiB per GPU, held until the process ends) instead of a caller
+ * workspace.  The caller still passes every input and output: logits [T][E], x [T][H], topk_idx / gates [T][k],
+ * stage / final_ [max_rows][H], out [T][H], all device pointers as in the calls above; results are bit-identical
+ * to those calls.  Calls no hipMalloc / hipFree and creates no stream or event: pipeline mode 0 is replaced by
+ * the size-chosen mode, and with event profiling enabled the call is refused (MONTA_ERR_INVALID).  Problems
+ * whose tables (monta_ws_layout.ws_bytes) exceed 16 MiB are refused with MONTA_ERR_TOO_LARGE before any GPU
+ * work; the five named workloads need at most 10.2 MiB.  Every call on one GPU shares that GPU's array: the
+ * counters in it are cleared by a small kernel at the start of each call, the tables are overwritten, and two
+ * calls that overlap in time on one GPU (different streams or threads) race -- the caller must order them. */
+int monta_route_dispatch_combine_static(const monta_cfg *cfg, const float *logits, const void *x, int32_t *topk_idx,
+                                        float *gates, void *stage, void *final_, void *out, void *stream);
 
 /* ---- the second AllToAll, mirrored (section "Pipelining", end of the paragraph on the Drop / AllGather
  * transform: the paper applies the same split to the second AllToAll) ----

@@ -73,7 +73,7 @@ EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "m
            "monta_unregather_combine", "monta_allgather", "monta_set_pipeline_mode",
            "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
            "monta_profile_read", "monta_plan_chunk_times", "monta_plan_strategy", "monta_strerror",
-           "monta_last_hip_error", "monta_shutdown"]
+           "monta_last_hip_error", "monta_shutdown", "monta_route_dispatch_combine_static"]
 
 _lib = None
 
@@ -119,6 +119,7 @@ def lib() -> ctypes.CDLL:
         L.monta_strerror.restype = ctypes.c_char_p
         L.monta_last_hip_error.argtypes = []
         L.monta_shutdown.argtypes = []
+        L.monta_route_dispatch_combine_static.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp]
         for name in EXPORTS:
             if name != "monta_strerror":
                 getattr(L, name).restype = ctypes.c_int
@@ -236,6 +237,16 @@ def monta_route_dispatch_regather(cfg, logits, x, topk_idx, gates, stage, final_
         ctypes.byref(cfg), _ptr(logits, T * E * 4, "logits"), _ptr(x, T * row, "x"), _ptr(topk_idx, T * k * 4, "topk_idx"),
         _ptr(gates, T * k * 4, "gates"), _ptr(stage, L.max_rows * row, "stage"), _ptr(final_, L.max_rows * row, "final_"),
         _ptr(ws, L.ws_bytes, "ws"), _stream(stream)), "monta_route_dispatch_regather")
+
+
+def monta_route_dispatch_combine_static(cfg, logits, x, topk_idx, gates, stage, final_, out, stream=None):
+    L = monta_ws_layout_query(cfg)
+    T, E, k = cfg.tokens, cfg.experts, cfg.top_k
+    row = cfg.hidden * _bpe(cfg)
+    _check(lib().monta_route_dispatch_combine_static(
+        ctypes.byref(cfg), _ptr(logits, T * E * 4, "logits"), _ptr(x, T * row, "x"), _ptr(topk_idx, T * k * 4, "topk_idx"),
+        _ptr(gates, T * k * 4, "gates"), _ptr(stage, L.max_rows * row, "stage"), _ptr(final_, L.max_rows * row, "final_"),
+        _ptr(out, T * row, "out"), _stream(stream)), "monta_route_dispatch_combine_static")
 
 
 def monta_combine(cfg, y, gates, out, ws, stream=None):

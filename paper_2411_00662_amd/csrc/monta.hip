@@ -705,6 +705,26 @@ int route_dispatch_regather_impl(const Geometry &g, const float *logits, const v
     return launch_regather(g, p, stage, final_, s.S - 1, st);
 }
 
+int combine_impl(const Geometry &g, int dtype, const void *y, const float *gates, void *out, const void *ws, hipStream_t st)
+{
+    const Shape &s = g.s;
+    const PlanPtrs p = plan_ptrs(g, ws);
+    ProfScope ps(MONTA_K_COMBINE, st);
+    const dim3 grid(mover_grid(s, s.T)), block(kMoverThreads);
+    const bool wide = s.vpr > kCombineWideVpr;   // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
+    const u32x4 *yv = static_cast<const u32x4 *>(y);
+    u32x4 *ov = static_cast<u32x4 *>(out);
+    if (dtype == MONTA_BF16) {
+        if (wide) hipLaunchKernelGGL((combine_kernel<true, 4>), grid, block, 0, st, yv, gates, ov, p, s);
+        else hipLaunchKernelGGL((combine_kernel<true, 2>), grid, block, 0, st, yv, gates, ov, p, s);
+    } else {
+        if (wide) hipLaunchKernelGGL((combine_kernel<false, 4>), grid, block, 0, st, yv, gates, ov, p, s);
+        else hipLaunchKernelGGL((combine_kernel<false, 2>), grid, block, 0, st, yv, gates, ov, p, s);
+    }
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -910,23 +930,7 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
     if ((rc = check_act_ptrs(y, out))) return rc;
     if (y == out) return MONTA_ERR_INVALID;
     if ((rc = check_ws(ws))) return rc;
-    const Shape &s = g.s;
-    const PlanPtrs p = plan_ptrs(g, ws);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    ProfScope ps(MONTA_K_COMBINE, st);
-    const dim3 grid(mover_grid(s, s.T)), block(kMoverThreads);
-    const bool wide = s.vpr > kCombineWideVpr;   // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
-    const u32x4 *yv = static_cast<const u32x4 *>(y);
-    u32x4 *ov = static_cast<u32x4 *>(out);
-    if (cfg->dtype == MONTA_BF16) {
-        if (wide) hipLaunchKernelGGL((combine_kernel<true, 4>), grid, block, 0, st, yv, gates, ov, p, s);
-        else hipLaunchKernelGGL((combine_kernel<true, 2>), grid, block, 0, st, yv, gates, ov, p, s);
-    } else {
-        if (wide) hipLaunchKernelGGL((combine_kernel<false, 4>), grid, block, 0, st, yv, gates, ov, p, s);
-        else hipLaunchKernelGGL((combine_kernel<false, 2>), grid, block, 0, st, yv, gates, ov, p, s);
-    }
-    HIP_TRY(hipGetLastError());
-    return MONTA_OK;
+    return combine_impl(g, cfg->dtype, y, gates, out, ws, static_cast<hipStream_t>(stream));
 }
 
 int monta_allgather(const monta_cfg *cfg, const void *stage, void *gathered, const void *ws, int slice, void *stream)
@@ -1055,6 +1059,67 @@ int monta_unregather_combine(const monta_cfg *cfg, const void *y, void *y_stage,
     return MONTA_OK;
 }
 
+// ---- one entry point that allocates nothing -------------------------------------------------------
+//
+// The plan tables of the whole step live in a file-scope device array instead of a caller workspace.
+// In host code the array's name is only a stand-in for the symbol: the device address is looked up once
+// per device (every GPU holds its own copy at its own address) and only that address is ever handed to
+// kernels.
+
+constexpr size_t kStaticScratchBytes = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[64] = {nullptr};
+
+int static_scratch(void **out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return MONTA_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));      // the current device's copy of the array
+        if (!ptr) return MONTA_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MONTA_OK;
+}
+
+}  // namespace
+
+int monta_route_dispatch_combine_static(const monta_cfg *cfg, const float *logits, const void *x, int32_t *topk_idx,
+                                        float *gates, void *stage, void *final_, void *out, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (!logits || !topk_idx || !gates) return MONTA_ERR_NULL;
+    if (misaligned(logits, 4) || misaligned(topk_idx, 4) || misaligned(gates, 4)) return MONTA_ERR_ALIGN;
+    if ((rc = check_act_ptrs(x, stage))) return rc;
+    if ((rc = check_act_ptrs(final_, out))) return rc;
+    if (stage == final_ || final_ == out || stage == out || x == out) return MONTA_ERR_INVALID;
+    monta_ws_layout L;
+    fill_layout(g, &L);
+    if ((size_t)L.ws_bytes > kStaticScratchBytes) return MONTA_ERR_TOO_LARGE;
+    // event profiling creates events per launch and the two-stream pipeline creates a stream: neither belongs
+    // in a call that must not allocate
+    if (g_prof_on.load()) return MONTA_ERR_INVALID;
+    if (g.modes.pipeline == 0) g.modes.pipeline = -1;
+    void *ws = nullptr;
+    if ((rc = static_scratch(&ws))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the array keeps the previous call's contents (possibly of another shape): put the counters back to zero
+    hipLaunchKernelGGL(ws_init_kernel, dim3(1), dim3(kWave), 0, st, plan_ptrs(g, ws).meta);
+    HIP_TRY(hipGetLastError());
+    if ((rc = route_dispatch_regather_impl(g, logits, x, topk_idx, gates, stage, final_, ws, st))) return rc;
+    return combine_impl(g, cfg->dtype, final_, gates, out, ws, st);
+}
+
 int monta_set_pipeline_mode(int mode)
 {
     if (mode < -1 || mode > 2) return MONTA_ERR_INVALID;
@@ -1137,6 +1202,7 @@ const char *monta_strerror(int code)
         case MONTA_ERR_NULL: return "required pointer is NULL";
         case MONTA_ERR_HIP: return "HIP runtime call failed (see monta_last_hip_error)";
         case MONTA_ERR_ALIGN: return "pointer is not aligned as required";
+        case MONTA_ERR_TOO_LARGE: return "problem needs more plan-table space than the library's static scratch array holds (16 MiB)";
         default: return "unknown monta status";
     }
 }

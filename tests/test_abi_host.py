@@ -179,3 +179,16 @@ def test_build_refuses_kernels_that_spill():
         "k.hpp:9:0: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n")
     assert scratch_users(remarks) == [("kernel_a", 352)]
     assert scratch_users("") == []
+
+
+def test_static_scratch_entry_point_refuses_oversized_problems_on_the_host():
+    """The plan tables of 4M pairs do not fit the 16 MiB static array: refused before any GPU call."""
+    lib = m.binding.lib()
+    cfg = m.make_cfg(1 << 19, 64, m.BF16, 64, 8, 8, 4, 8, 0.0)
+    assert m.monta_ws_layout_query(cfg).ws_bytes > (16 << 20)
+    fake = ctypes.c_void_p(0x1000)
+    rc = lib.monta_route_dispatch_combine_static(ctypes.byref(cfg), fake, fake, fake, fake, ctypes.c_void_p(0x2000),
+                                                 ctypes.c_void_p(0x3000), ctypes.c_void_p(0x4000), None)
+    assert rc == -6 and "static" in m.monta_strerror(rc)
+    # argument checks come first
+    assert lib.monta_route_dispatch_combine_static(ctypes.byref(cfg), None, fake, fake, fake, fake, fake, fake, None) == -3
