@@ -79,8 +79,8 @@ int64_t capacity_of(const monta_cfg *c)
 size_t route_lds_bytes(int TB, int E, int k)
 {
     const int NW = TB > kWave ? TB / kWave : 1;
-    size_t b = ((size_t)TB * (E | 1) * 4 + (size_t)TB * k * 4 + 7) & ~(size_t)7;
-    return b + (size_t)E * NW * 8;
+    size_t b = ((size_t)TB * (E | 1) * 4 + (size_t)TB * k * 4 + 7) & ~(size_t)7;    // logits tile, selections
+    return b + (size_t)E * NW * 8 + (size_t)TB * k * 8 + (size_t)TB * 8;            // bit masks, weights, denominators
 }
 
 int validate(const monta_cfg *c, Geometry *g)
@@ -619,7 +619,7 @@ int effective_pipeline_mode(const Geometry &g)
 {
     if (g.modes.pipeline >= 0) return g.modes.pipeline;
     const int64_t slice_bytes = slice_rows_bound(g, 1) * g.row_bytes;      // rows one slice may put into STAGE
-    return slice_bytes > kSerialSliceBytes ? 2 : 1;
+    return slice_bytes >= kSerialSliceBytes ? 2 : 1;
 }
 
 int route_impl(const Geometry &g, const float *logits, int32_t *topk_idx, float *gates, void *ws, hipStream_t st)
@@ -714,6 +714,20 @@ int combine_impl(const Geometry &g, int dtype, const void *y, const float *gates
     const bool wide = s.vpr > kCombineWideVpr;   // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
     const u32x4 *yv = static_cast<const u32x4 *>(y);
     u32x4 *ov = static_cast<u32x4 *>(out);
+    // With three or more choices per token the software-pipelined form wins (measured on MI355X, 65536 tokens of
+    // 14 KiB, top-8 with drops: 802 -> 707 us); with one or two there is nothing to pipeline and its extra
+    // registers cost 2-4 %.  It needs the token's k positions to fit the lanes that share its row.
+    if (s.k >= 3 && s.k <= s.lpr) {
+        if (dtype == MONTA_BF16) {
+            if (wide) hipLaunchKernelGGL((combine_pf_kernel<true, 4>), grid, block, 0, st, yv, gates, ov, p, s);
+            else hipLaunchKernelGGL((combine_pf_kernel<true, 2>), grid, block, 0, st, yv, gates, ov, p, s);
+        } else {
+            if (wide) hipLaunchKernelGGL((combine_pf_kernel<false, 4>), grid, block, 0, st, yv, gates, ov, p, s);
+            else hipLaunchKernelGGL((combine_pf_kernel<false, 2>), grid, block, 0, st, yv, gates, ov, p, s);
+        }
+        HIP_TRY(hipGetLastError());
+        return MONTA_OK;
+    }
     if (dtype == MONTA_BF16) {
         if (wide) hipLaunchKernelGGL((combine_kernel<true, 4>), grid, block, 0, st, yv, gates, ov, p, s);
         else hipLaunchKernelGGL((combine_kernel<true, 2>), grid, block, 0, st, yv, gates, ov, p, s);

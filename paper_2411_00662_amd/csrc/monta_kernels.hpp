@@ -121,6 +121,8 @@ __global__ __launch_bounds__(1024) void route_plan_kernel(const float *__restric
     int *s_sel = reinterpret_cast<int *>(s_l + (size_t)TB * stride);
     unsigned long long *s_mask = reinterpret_cast<unsigned long long *>(
         smem + (((size_t)TB * stride * 4 + (size_t)TB * k * 4 + 7) & ~(size_t)7));
+    double *s_w = reinterpret_cast<double *>(s_mask + (size_t)E * NW);     // [TB][k] unnormalised weights
+    double *s_den = s_w + (size_t)TB * k;                                  // [TB] softmax denominators (renorm = 0)
     __shared__ int s_last;
     __shared__ int s_cnt[256];
     __shared__ int s_off[257];
@@ -152,11 +154,10 @@ __global__ __launch_bounds__(1024) void route_plan_kernel(const float *__restric
     const unsigned long long tbit = 1ull << (tok & 63);
     const int t = t_begin + tok;
     const bool active = tok < nt;
-    const bool leader = active && sub == 0;
     if (active) {
         const float *row = s_l + tok * stride;
         int *sel = s_sel + tok * k;
-        float pv = INFINITY;
+        float pv = INFINITY, top_logit = 0.f;
         int pi = -1;
         for (int j = 0; j < k; ++j) {
             int best = -1;
@@ -182,57 +183,58 @@ __global__ __launch_bounds__(1024) void route_plan_kernel(const float *__restric
             if (best < 0) best = (pi + 1 < E) ? pi + 1 : E - 1;   // unreachable for k <= E; keeps indices in range
             pv = bv;
             pi = best;
+            if (j == 0) top_logit = bv;
             if (sub == 0) {
                 sel[j] = best;
                 topk_idx[(size_t)t * k + j] = best;
                 atomicOr(&s_mask[best * NW + tword], tbit);
             }
         }
-    }
-    if (leader) {
-        const float *row = s_l + tok * stride;
-        const int *sel = s_sel + tok * k;
-        // gates: w_j = exp(l_j - l_0) in fp64, denominator summed in j (or expert) order, one rounding to fp32.
-        // The first KW weights stay in registers; w_0 = exp(0) = 1 needs no call.
-        constexpr int KW = 8;
-        const double top = (double)row[sel[0]];
-        double w[KW];
-        double denom = 0.0;
-#pragma unroll
-        for (int j = 0; j < KW; ++j) {
-            w[j] = 0.0;
-            if (j < k) {
-                w[j] = j == 0 ? 1.0 : exp((double)row[sel[j]] - top);
-                if (s.renorm) denom += w[j];
-            }
+        if (!s.renorm) {
+            // softmax over all E: the token's lanes each sum their experts, then add up across the lanes
+            double part = 0.0;
+            for (int e = sub; e < E; e += L) part += exp((double)row[e] - (double)top_logit);
+            for (int mk = 1; mk < L; mk <<= 1) part += __shfl_xor(part, mk, kWave);
+            if (sub == 0) s_den[tok] = part;
         }
-        if (s.renorm) {
-            for (int j = KW; j < k; ++j) denom += exp((double)row[sel[j]] - top);
-        } else {
-            for (int e = 0; e < E; ++e) denom += exp((double)row[e] - top);
-        }
-#pragma unroll
-        for (int j = 0; j < KW; ++j)
-            if (j < k) gates[(size_t)t * k + j] = (float)(w[j] / denom);
-        for (int j = KW; j < k; ++j)
-            gates[(size_t)t * k + j] = (float)(exp((double)row[sel[j]] - top) / denom);
     }
     __syncthreads();
+    // gates: w_j = exp(l_j - l_0) in fp64 (w_0 = 1 needs no call), one (token, choice) pair per lane so that every
+    // lane of the workgroup has an exp to do, not only one lane per token; then the denominator is summed in j
+    // order (or taken from the sum over all experts), one division, one rounding to fp32.
+    const int npairs = nt * k;
+    for (int idx = tid; idx < npairs; idx += blockDim.x) {
+        const int tk = idx / k, j = idx - tk * k;
+        const float *row = s_l + tk * stride;
+        const int *sel = s_sel + tk * k;
+        s_w[idx] = j == 0 ? 1.0 : exp((double)row[sel[j]] - (double)row[sel[0]]);
+    }
+    __syncthreads();
+    for (int idx = tid; idx < npairs; idx += blockDim.x) {
+        const int tk = idx / k;
+        double denom = 0.0;
+        if (s.renorm) {
+            const double *wt = s_w + tk * k;
+            for (int j = 0; j < k; ++j) denom += wt[j];
+        } else {
+            denom = s_den[tk];
+        }
+        gates[(size_t)t_begin * k + idx] = (float)(s_w[idx] / denom);
+    }
 
     for (int e = tid; e < E; e += blockDim.x) {
         int c = 0;
         for (int w = 0; w < NW; ++w) c += __popcll(s_mask[e * NW + w]);
         p.block_counts[(size_t)b * E + e] = c;
     }
-    if (leader) {
-        const unsigned long long below = tbit - 1ull;
-        for (int j = 0; j < k; ++j) {
-            const int e = s_sel[tok * k + j];
-            int r = 0;
-            for (int w = 0; w < tword; ++w) r += __popcll(s_mask[e * NW + w]);
-            r += __popcll(s_mask[e * NW + tword] & below);
-            p.local_rank[(size_t)t * k + j] = r;    // rank inside the workgroup; the positions kernels finish it
-        }
+    for (int idx = tid; idx < npairs; idx += blockDim.x) {      // one pair per lane again
+        const int tk = idx / k;
+        const int e = s_sel[idx];
+        const int word = tk >> 6;
+        int r = 0;
+        for (int w = 0; w < word; ++w) r += __popcll(s_mask[e * NW + w]);
+        r += __popcll(s_mask[e * NW + word] & ((1ull << (tk & 63)) - 1ull));
+        p.local_rank[(size_t)t_begin * k + idx] = r;    // rank inside the workgroup; the positions kernels finish it
     }
 
     if (b == 0 && tid == 0) p.meta[META_ALIVE] = 0;   // counted by the kernel that finishes the positions
@@ -378,6 +380,40 @@ struct BlockPlan {
     int R, unit_row0;
 };
 
+// One lane's share of the histogram-table reduction of block_plan: the counters of expert e in blocks bl, bl + bstep,
+// ..., LD loads requested before any is added up.
+struct BlockSums {
+    int total, before, unit, pre, sbefore, sin;
+};
+template <int LD>
+__device__ __forceinline__ BlockSums sum_blocks(const int32_t *__restrict__ block_counts, int E, int e, int bl, int bstep,
+                                                int nblk, int b, int first, int last, int sfirst, int slast)
+{
+    BlockSums a = {0, 0, 0, 0, 0, 0};
+    for (int bb0 = bl; bb0 < nblk; bb0 += bstep * LD) {
+        int cnt[LD];
+#pragma unroll
+        for (int q = 0; q < LD; ++q) {
+            const int bb = bb0 + q * bstep;
+            cnt[q] = bb < nblk ? block_counts[(size_t)bb * E + e] : 0;
+        }
+#pragma unroll
+        for (int q = 0; q < LD; ++q) {
+            const int bb = bb0 + q * bstep;
+            const int c = cnt[q];
+            a.total += c;
+            if (bb < first) a.before += c;
+            else if (bb < last) {
+                a.unit += c;
+                if (bb < b) a.pre += c;
+            }
+            if (bb < sfirst) a.sbefore += c;
+            else if (bb < slast) a.sin += c;
+        }
+    }
+    return a;
+}
+
 // Every workgroup that calls this re-reads the whole [num_blocks][E] histogram table (a few KiB,
 // L2 resident) and reduces it to four sums per expert; two wave scans over the experts then give
 // the expert offsets and the unit's STAGE block offsets, using the telescoped form
@@ -398,30 +434,19 @@ __device__ __forceinline__ void block_plan(BlockPlan &bp, int b, const PlanPtrs 
         const int sfirst = (u / s.tp) * s.tp * s.bpu, slast = sfirst + s.tp * s.bpu;   // blocks of this slice
         const int nthr = blockDim.x;
         if (nthr % E == 0) {
-            // A lane meets one expert only and sums in registers, with one LDS update at the end.
-            // Every workgroup reads the same table: each starts at a different chunk and wraps around,
-            // so that at any moment the workgroups pull from different L2 channels.
+            // A lane meets one expert only and sums in registers, with one LDS update at the end.  The table
+            // sits in the L2: a load costs hundreds of cycles, so a lane asks for LD of its counters at a time
+            // before it adds any of them up (one at a time the loop is a chain of L2 round trips; measured on a
+            // table of 256 x 64 counters the kernel takes 26 us this way against 32 us).  Small tables take the
+            // plain loop, which needs fewer registers.
             const int e = tid % E;
-            int a_total = 0, a_before = 0, a_unit = 0, a_pre = 0, a_sbefore = 0, a_sin = 0;
-            const int bstep = nthr / E;
-            const int nchunks = (total + nthr - 1) / nthr;
-            int c = (int)(((unsigned)b * 7u) % (unsigned)nchunks);
-            for (int n = 0; n < nchunks; ++n) {
-                const int i = c * nthr + tid;
-                if (i < total) {
-                    const int bb = c * bstep + tid / E;
-                    const int cnt = p.block_counts[i];
-                    a_total += cnt;
-                    if (bb < first) a_before += cnt;
-                    else if (bb < last) {
-                        a_unit += cnt;
-                        if (bb < b) a_pre += cnt;
-                    }
-                    if (bb < sfirst) a_sbefore += cnt;
-                    else if (bb < slast) a_sin += cnt;
-                }
-                if (++c == nchunks) c = 0;
-            }
+            const int bl = tid / E, bstep = nthr / E;            // this lane's first block and its stride
+            const int nblk = s.num_blocks;
+            const BlockSums a = nblk > 4 * bstep
+                                    ? sum_blocks<16>(p.block_counts, E, e, bl, bstep, nblk, b, first, last, sfirst, slast)
+                                    : sum_blocks<1>(p.block_counts, E, e, bl, bstep, nblk, b, first, last, sfirst, slast);
+            const int a_total = a.total, a_before = a.before, a_unit = a.unit, a_pre = a.pre, a_sbefore = a.sbefore,
+                      a_sin = a.sin;
             if (a_sbefore) atomicAdd(&bp.sbefore[e], a_sbefore);
             if (a_sin) atomicAdd(&bp.sin[e], a_sin);
             if (a_total) atomicAdd(&bp.total[e], a_total);
@@ -854,22 +879,25 @@ __global__ __launch_bounds__(kMoverThreads) void pack_regather_kernel(const u32x
 __device__ __forceinline__ double bf16_lo(unsigned int w) { return (double)__uint_as_float(w << 16); }
 __device__ __forceinline__ double bf16_hi(unsigned int w) { return (double)__uint_as_float(w & 0xffff0000u); }
 
-// fp64 -> bf16 bits with ONE rounding (nearest, ties to even).  Going through fp32
-// with two nearest roundings could round twice, so the fp32 step is turned into
-// round-to-odd: truncate toward zero and set the last bit when anything was lost.
-// A round-to-odd value with 16 spare bits rounds to bf16 exactly like the fp64
-// value itself.  Overflow, underflow and infinities fall out of the same path.
+// fp64 -> bf16 bits with ONE rounding (nearest, ties to even).  The value first goes to fp32 (nearest-even, one
+// hardware conversion).  Rounding is monotone and every midpoint between two bf16 values is an fp32 number, so
+// unless the fp32 value IS such a midpoint (low 16 bits 0x8000) it lies on the same side of every midpoint as
+// the fp64 value, and rounding it to nearest gives the fp64 value's bf16: add 0x8000 and drop the low half.
+// Only in the midpoint case (one in 65536) the fp32 step may have hidden on which side the fp64 value lay: the
+// slow branch compares the two and rounds down, up, or (a true tie) to even.  Overflow, underflow and
+// infinities fall out of the same arithmetic; NaN is mapped to the canonical quiet NaN.
 __device__ __forceinline__ unsigned int f64_to_bf16_rne(double d)
 {
-    const float f = (float)d;                       // nearest
-    const double back = (double)f;
-    unsigned int u = __float_as_uint(f);
-    if (back != d) {                                // inexact (also true for NaN, handled below)
-        if (__builtin_fabs(back) > __builtin_fabs(d)) u -= 1u;   // step back toward zero: truncation
-        u |= 1u;                                    // sticky bit
+    const float f = (float)d;                       // nearest-even
+    const unsigned int u = __float_as_uint(f);
+    unsigned int r = (u + 0x8000u) >> 16;
+    if (__builtin_expect((u & 0xffffu) == 0x8000u, 0)) {
+        const double back = (double)f;
+        if (back == d) r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                 // true tie: to even
+        else if (__builtin_fabs(back) > __builtin_fabs(d)) r = u >> 16;            // below the midpoint
+        else r = (u >> 16) + 1u;                                                   // above it
     }
-    const unsigned int r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-    return d != d ? 0x7fc0u : r;
+    return f != f ? 0x7fc0u : r;
 }
 
 // out[t] = sum_j gate[t,j] * y[pos_final[t,j]] over kept j in ascending order.
@@ -943,6 +971,123 @@ __device__ __forceinline__ void combine_rows_t(const u32x4 *__restrict__ y, cons
             }
         }
     }
+}
+
+// The same scale-add with the row reads software-pipelined.  One wave's time on a token is a chain of
+// memory latencies: position and gate of choice j, then the row they point to, then the next choice.  Here
+// the first k lanes of a row's lane group fetch the token's k positions and gates in one go (a ballot of
+// their validity gives the kept choices as a bit mask, shuffles hand each one to all lanes), and the row of
+// the next kept choice is requested before the current one is added, so two rows' loads are in flight per
+// lane and the fp64 arithmetic runs under them.  Needs k <= lanes per row (the host checks).  Same order of
+// additions, same result.
+template <bool BF16, int NV, bool NTL, bool NTS>
+__device__ __forceinline__ void combine_rows_pf_t(const u32x4 *__restrict__ y, const float *__restrict__ gates,
+                                                  u32x4 *__restrict__ out, const int32_t *__restrict__ pos_table,
+                                                  const Shape &s, int t0, int nt, int wg, int nwg)
+{
+    constexpr int NF = BF16 ? 8 : 4;            // accumulators per vector
+    const int lpr = s.lpr, vpr = s.vpr, k = s.k;
+    const int rows_per_wg = kMoverThreads / lpr;
+    const int sub = threadIdx.x / lpr, lane = threadIdx.x - sub * lpr;
+    const int wl = threadIdx.x & (kWave - 1);
+    const int gbase = lpr >= kWave ? 0 : (wl & ~(lpr - 1));     // first lane, inside the wave, of this lane's row group
+    const int gl = wl - gbase;                                  // this lane's index in it
+    const unsigned int kmask = k >= 32 ? 0xffffffffu : ((1u << k) - 1u);
+    for (int i = wg * rows_per_wg + sub; i < nt; i += nwg * rows_per_wg) {
+        const int t = t0 + nt - 1 - i;
+        u32x4 *dst = out + (size_t)t * vpr;
+        int my_pos = -1;
+        float my_g = 0.f;
+        if (gl < k) {
+            my_pos = pos_table[(size_t)t * k + gl];
+            my_g = gates[(size_t)t * k + gl];
+        }
+        const unsigned long long valid = __ballot((unsigned)my_pos < (unsigned)s.max_rows);
+        const unsigned int kept = (unsigned int)(valid >> gbase) & kmask;      // bit j: choice j of this token is kept
+        // every lane of the group walks every pass, also lanes past the end of a short row: the shuffles below
+        // read the positions from the group's first k lanes, which must therefore stay active
+        for (int vbase = 0; vbase < vpr; vbase += lpr * NV) {
+            const int v0 = vbase + lane;
+            double acc[NV][NF];
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+#pragma unroll
+                for (int f = 0; f < NF; ++f) acc[q][f] = 0.0;
+            unsigned int rem = kept;
+            u32x4 cur[NV];
+            float g_cur = 0.f;
+            bool have = rem != 0;
+            if (have) {
+                const int j = __builtin_ctz(rem);
+                rem &= rem - 1;
+                const int pf = __shfl(my_pos, gbase + j, kWave);
+                g_cur = __shfl(my_g, gbase + j, kWave);
+                const u32x4 *src = y + (size_t)pf * vpr;
+#pragma unroll
+                for (int q = 0; q < NV; ++q)
+                    if (v0 + q * lpr < vpr) cur[q] = ld16<NTL>(src + v0 + q * lpr);
+            }
+            while (have) {
+                u32x4 nxt[NV];
+                float g_nxt = 0.f;
+                const bool have_nxt = rem != 0;
+                if (have_nxt) {
+                    const int j = __builtin_ctz(rem);
+                    rem &= rem - 1;
+                    const int pf = __shfl(my_pos, gbase + j, kWave);
+                    g_nxt = __shfl(my_g, gbase + j, kWave);
+                    const u32x4 *src = y + (size_t)pf * vpr;
+#pragma unroll
+                    for (int q = 0; q < NV; ++q)
+                        if (v0 + q * lpr < vpr) nxt[q] = ld16<NTL>(src + v0 + q * lpr);
+                }
+                const double gj = (double)g_cur;
+#pragma unroll
+                for (int q = 0; q < NV; ++q) {
+                    if (v0 + q * lpr < vpr) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            if (BF16) {
+                                acc[q][2 * c] = __builtin_fma(gj, bf16_lo(cur[q][c]), acc[q][2 * c]);
+                                acc[q][2 * c + 1] = __builtin_fma(gj, bf16_hi(cur[q][c]), acc[q][2 * c + 1]);
+                            } else {
+                                acc[q][c] = __builtin_fma(gj, (double)__uint_as_float(cur[q][c]), acc[q][c]);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < NV; ++q) cur[q] = nxt[q];
+                g_cur = g_nxt;
+                have = have_nxt;
+            }
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                if (v0 + q * lpr < vpr) {
+                    u32x4 o;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        if (BF16)
+                            o[c] = f64_to_bf16_rne(acc[q][2 * c]) | (f64_to_bf16_rne(acc[q][2 * c + 1]) << 16);
+                        else
+                            o[c] = __float_as_uint((float)acc[q][c]);
+                    }
+                    st16<NTS>(dst + v0 + q * lpr, o);
+                }
+            }
+        }
+    }
+}
+
+template <bool BF16, int NV>
+__global__ __launch_bounds__(kMoverThreads) void combine_pf_kernel(const u32x4 *__restrict__ y,
+                                                                   const float *__restrict__ gates,
+                                                                   u32x4 *__restrict__ out, PlanPtrs p, Shape s)
+{
+    with_policy(s.cache & NT_COMB_LD, s.cache & NT_COMB_ST, [&](auto l, auto st) {
+        combine_rows_pf_t<BF16, NV, decltype(l)::value, decltype(st)::value>(y, gates, out, p.pos_final, s, 0, s.T,
+                                                                             blockIdx.x, gridDim.x);
+    });
 }
 
 template <bool BF16, int NV>

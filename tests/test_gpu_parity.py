@@ -335,6 +335,53 @@ def test_non_identity_experts_and_shared_gates(m):
         np.testing.assert_array_equal(out, ref_out)
 
 
+def test_combine_rounding_traps_at_bf16_midpoints(m):
+    """Sums that sit exactly on, or a hair beside, the midpoint between two bf16 values: rounding the fp64 sum
+    to fp32 first lands exactly on the midpoint, so a kernel that then rounded to nearest-even again would go
+    the wrong way.  Expected values follow from the construction (closed form), and the oracle must agree."""
+    import torch
+    from paper_2411_00662_amd import buffers as bufs
+    T, H, E, k = 512, 256, 4, 2
+    w = Workload("traps", T, H, BF16, E, k, 2, 2, 2, 0.0)
+    logits, x = workloads.make_inputs(w, seed=4)
+    ref = oracle.forward(logits, x, k=k, ep=2, tp=2, S=2, cf=0.0)
+    R = ref.plan.R
+    assert R == T * k
+    rng = np.random.default_rng(7)
+    # token t: out = g0 * 1.0 + g1 * y1 with g0 = a bf16 midpoint (9 significant bits, exact in fp32) and
+    # g1 * y1 = 0 (true tie), or +/- a term far below fp32 resolution of the sum (the trap)
+    mant = rng.integers(0, 128, size=T)                       # bf16 mantissa of the lower neighbour
+    expo = rng.integers(-6, 7, size=T)
+    sign = rng.choice([-1.0, 1.0], size=T)
+    lower = (1.0 + mant / 128.0) * 2.0 ** expo                # a bf16 value
+    mid = lower + 2.0 ** (expo - 8.0)                         # halfway to the next one
+    kind = rng.integers(0, 3, size=T)                         # 0 tie, 1 just above, 2 just below
+    tiny = np.float32(2.0 ** -40)
+    gates = np.zeros((T, k), np.float32)
+    gates[:, 0] = (sign * mid).astype(np.float32)
+    assert np.array_equal(gates[:, 0].astype(np.float64), sign * mid)
+    gates[:, 1] = np.where(kind == 0, 0.0, tiny * 2.0 ** expo).astype(np.float32)
+    y = np.zeros((R, H), np.float32)
+    pf = ref.plan.pos_final
+    y[pf[:, 0]] = 1.0
+    y[pf[:, 1]] = (np.where(kind == 1, 1.0, -1.0) * sign)[:, None]
+    ybits = workloads.f32_to_bf16_bits(y)
+    up = lower + 2.0 ** (expo - 7.0)
+    even_is_lower = (mant % 2 == 0)
+    want = np.where(kind == 1, up, np.where(kind == 2, lower, np.where(even_is_lower, lower, up))) * sign
+    want_bits = workloads.f32_to_bf16_bits(np.repeat(want.astype(np.float32)[:, None], H, axis=1))
+    ref_out = oracle.combine(ybits, gates, pf)
+    np.testing.assert_array_equal(ref_out, want_bits)          # the oracle against the closed form
+    cfg = cfg_of(m, w)
+    b = m.alloc_buffers(cfg, logits, x, canary=0)
+    m.monta_route(cfg, b.logits, b.topk_idx, b.gates, b.ws)
+    b.gates.copy_(torch.from_numpy(gates).cuda())
+    b.final[:R].copy_(bufs.to_device_act(cfg, ybits))
+    m.monta_combine(cfg, b.final, b.gates, b.out, b.ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bufs.to_host_act(cfg, b.out), want_bits)
+
+
 def test_workspace_reuse_across_different_inputs(m):
     """The ticket counter and every table must be rebuilt on each call."""
     import torch
