@@ -189,18 +189,28 @@ def measure(args, w, steps, warmup, full):
                              "us_per_step": avg * n / (prof_steps + 3)}
         m.monta_profile_reset()
         S = w.slices
-        per_launch = {"pack": None, "regather": None, "pack_regather": None, "combine": ab["combine"],
-                      "plan_pack": ab["pack_s"][0] + ab["plan"], "gate": ab.get("gate")}
-        co_scheduled = "pack_regather" in kernels or "plan_pack" in kernels
-        if "pack" in kernels:
-            npk = round(kernels["pack"]["launches_per_step"])
-            per_launch["pack"] = (ab["pack_s"][0] if co_scheduled else sum(ab["pack_s"])) / npk
-        if "regather" in kernels:
-            nrg = round(kernels["regather"]["launches_per_step"])
-            per_launch["regather"] = (ab["regather_s"][S - 1] if co_scheduled else sum(ab["regather_s"])) / nrg
-        if "pack_regather" in kernels:
-            tot = sum(ab["pack_s"][j] + ab["regather_s"][j - 1] for j in range(1, S))
-            per_launch["pack_regather"] = tot / (S - 1)
+        # bytes per launch of every kernel class, from the launch sequence the library reports for this problem
+        pmode, first, spg, fused = m.monta_pipeline_query(cfg)
+        groups = [range(0, first)] + [range(lo, min(lo + spg, S)) for lo in range(first, S, spg)]
+        pack_g = [sum(ab["pack_s"][j] for j in gr) for gr in groups]
+        reg_g = [sum(ab["regather_s"][j] for j in gr) for gr in groups]
+        G = len(groups)
+        seq = [("plan_pack" if fused else "pack", pack_g[0] + (ab["plan"] if fused else 0))]
+        if pmode == 1:
+            seq += [("pack_regather", pack_g[gi] + reg_g[gi - 1]) for gi in range(1, G)] + [("regather", reg_g[G - 1])]
+        else:
+            seq += [("regather", reg_g[0])]
+            for gi in range(1, G):
+                seq += [("pack", pack_g[gi]), ("regather", reg_g[gi])]
+        per_launch = {"combine": ab["combine"], "gate": ab.get("gate")}
+        for kname in ("pack", "regather", "pack_regather", "plan_pack"):
+            vals = [v for n_, v in seq if n_ == kname]
+            per_launch[kname] = sum(vals) / len(vals) if vals else None
+        if experts and args.expert_overlap:      # the overlapped expert form runs the co-scheduled pipeline slice by slice
+            per_launch["pack"] = ab["pack_s"][0]
+            per_launch["regather"] = ab["regather_s"][S - 1]
+            if S > 1:
+                per_launch["pack_regather"] = sum(ab["pack_s"][j] + ab["regather_s"][j - 1] for j in range(1, S)) / (S - 1)
         if mirror:
             per_launch["unregather"] = ab["unregather_s"][0]
             per_launch["combine"] = ab["combine_s"][S - 1]
@@ -246,6 +256,7 @@ def measure(args, w, steps, warmup, full):
                 v[kk] = round(v[kk], 3)
         res["roofline"] = roofline
         res["kernels"] = kernels
+        res["pipeline"] = {"realisation": pmode, "first_launch_slices": first, "slices_per_launch": spg, "plan_fused_with_first_pack": fused}
 
     if args.calib_copy_mib > 0:
         nbytes = args.calib_copy_mib << 20
@@ -395,7 +406,7 @@ def main():
         "config": {"workload": w.name, "tokens": w.tokens, "hidden": w.hidden, "experts": w.experts,
                    "top_k": w.top_k, "ep": w.ep, "tp": w.tp, "slices": w.slices,
                    "capacity_factor": w.capacity_factor, "kept_rows": ab["R"], "alive_tokens": ab["alive"],
-                   "pipeline_mode": mode_label(res["mode"]), "hip_graph": res["use_graph"], "return_path": args.return_path,
+                   "pipeline_mode": mode_label(res["mode"]), "pipeline": res.get("pipeline"), "hip_graph": res["use_graph"], "return_path": args.return_path,
                    "padded": w.padded, "gate": bool(args.gate), "expert_layer": bool(args.experts),
                    "expert_overlap": int(args.expert_overlap), "parallelism": "1 GPU, virtual ep/tp"},
         "effective_GBps": round(eff_gbps, 1), "pct_of_hbm_peak": round(100 * eff_gbps / HBM_PEAK_GBPS, 2),

@@ -269,11 +269,22 @@ int monta_unregather_combine(const monta_cfg *cfg, const void *y, void *y_stage,
  *   1  one stream, co-scheduled grids: launch j does regather(j-1) and pack(j) in
  *      disjoint workgroups of one grid (S+1 launches, no events);
  *   2  one stream, strictly serial pack(0), regather(0), pack(1), ...
- *  -1  (default) chosen per call from what one slice moves: 1 while a slice's copies are
- *      short enough for the launch boundaries to matter (up to 256 MiB per slice), 2 above.
+ *  -1  (default) chosen per call from the sizes, as the paper's planner picks its chunk count from
+ *      the traffic: consecutive slices are grouped into one launch until a launch's share of STAGE
+ *      reaches 256 MiB; the groups run as in 1 while their copies are short, as in 2 once a group
+ *      moves 192 MiB or more.  A problem that fits one group runs in three launches: plan + pack of
+ *      the first slices (about one round of workgroups), pack of the rest co-scheduled with the
+ *      regather of the first, regather of the rest.
+ * With 0, 1 or 2 every launch covers exactly one slice.  STAGE keeps its [slice][tp rank][expert]
+ * layout in every case; only the launch grouping differs.
  * Returns MONTA_ERR_INVALID for other values.  Process-wide. */
 int monta_set_pipeline_mode(int mode);
 int monta_get_pipeline_mode(void);
+/* Host only: what monta_route_dispatch_regather would do for cfg under the current switch: the realisation
+ * (0, 1 or 2), the slices the first launch covers, the slices each later launch covers, and whether the kernel
+ * that finishes the plan also packs the first launch's slices.  Benchmarks use it to attribute bytes to launches. */
+int monta_pipeline_query(const monta_cfg *cfg, int32_t *mode, int32_t *first_slices, int32_t *slices_per_launch,
+                         int32_t *plan_fused);
 
 /* How monta_route builds the plan tables.  -1 (default): when the per-workgroup
  * histogram table is small (num_blocks * experts <= 65536) every workgroup of the

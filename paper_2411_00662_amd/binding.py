@@ -73,7 +73,7 @@ EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "m
            "monta_unregather_combine", "monta_allgather", "monta_set_pipeline_mode",
            "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
            "monta_profile_read", "monta_plan_chunk_times", "monta_plan_strategy", "monta_strerror",
-           "monta_last_hip_error", "monta_shutdown", "monta_route_dispatch_combine_static"]
+           "monta_last_hip_error", "monta_shutdown", "monta_route_dispatch_combine_static", "monta_pipeline_query"]
 
 _lib = None
 
@@ -119,6 +119,7 @@ def lib() -> ctypes.CDLL:
         L.monta_strerror.restype = ctypes.c_char_p
         L.monta_last_hip_error.argtypes = []
         L.monta_shutdown.argtypes = []
+        L.monta_pipeline_query.argtypes = [cfgp] + [ctypes.POINTER(ctypes.c_int32)] * 4
         L.monta_route_dispatch_combine_static.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp]
         for name in EXPORTS:
             if name != "monta_strerror":
@@ -295,6 +296,14 @@ def monta_set_pipeline_mode(mode: int):
 
 def monta_get_pipeline_mode() -> int:
     return int(lib().monta_get_pipeline_mode())
+
+
+def monta_pipeline_query(cfg):
+    """-> (mode, slices of the first launch, slices per later launch, plan fused with the first pack)."""
+    a, f, b, c = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().monta_pipeline_query(ctypes.byref(cfg), ctypes.byref(a), ctypes.byref(f), ctypes.byref(b), ctypes.byref(c)),
+           "monta_pipeline_query")
+    return a.value, f.value, b.value, bool(c.value)
 
 
 def monta_set_plan_mode(mode: int):

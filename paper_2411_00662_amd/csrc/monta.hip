@@ -20,8 +20,6 @@ namespace {
 
 using namespace monta;
 
-// rows above this many 16-byte vectors (8 KiB) are combined with 4 vectors per lane and pass instead of 2
-constexpr int kCombineWideVpr = 2 * kMoverThreads;
 
 thread_local int g_last_hip = 0;
 std::atomic<int> g_pipeline_mode{-1};  // -1: chosen from the bytes one slice moves
@@ -342,7 +340,8 @@ int dev_state(int nslices, DevState **out)
 // ------------------------------------------------------------ launch shapes
 
 constexpr int kMaxMoverGrid = 1 << 16;
-constexpr int64_t kSerialSliceBytes = 256ll << 20;   // above this a slice's pack and regather run as two kernels
+constexpr int kResidentMoverWgs = 2048;         // mover workgroups the chip holds at once: 256 CUs x 8
+constexpr int64_t kGroupBytes = 256ll << 20;   // a launch group's share of STAGE: the size of the memory-side cache
 
 int mover_grid(const Shape &s, int64_t rows)
 {
@@ -368,12 +367,12 @@ int64_t slice_rows_bound(const Geometry &g, int nslices_covered)
     return r < g.max_rows ? r : g.max_rows;
 }
 
-int launch_pack(const Geometry &g, const PlanPtrs &p, const void *x, void *stage, int slice, hipStream_t st)
+// The launch helpers below take a range of slices [j0, j1).
+int launch_pack(const Geometry &g, const PlanPtrs &p, const void *x, void *stage, int j0, int j1, hipStream_t st)
 {
     const Shape &s = g.s;
     const int per_slice = s.tp * s.Tu;
-    const int t0 = slice < 0 ? 0 : slice * per_slice;
-    const int nt = slice < 0 ? s.T : per_slice;
+    const int t0 = j0 * per_slice, nt = (j1 - j0) * per_slice;
     ProfScope ps(MONTA_K_PACK, st);
     hipLaunchKernelGGL(pack_kernel, dim3(mover_grid(s, nt)), dim3(kMoverThreads), 0, st,
                        static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), p, s, t0, nt);
@@ -381,31 +380,29 @@ int launch_pack(const Geometry &g, const PlanPtrs &p, const void *x, void *stage
     return MONTA_OK;
 }
 
-int launch_regather(const Geometry &g, const PlanPtrs &p, const void *stage, void *fin, int slice, hipStream_t st)
+int launch_regather(const Geometry &g, const PlanPtrs &p, const void *stage, void *fin, int j0, int j1, hipStream_t st)
 {
     const Shape &s = g.s;
-    const int u0 = slice < 0 ? 0 : slice * s.tp;
-    const int u1 = slice < 0 ? s.U : (slice + 1) * s.tp;
-    const int64_t bound = slice_rows_bound(g, slice < 0 ? s.S : 1);
+    const int64_t bound = slice_rows_bound(g, j1 - j0);
     ProfScope ps(MONTA_K_REGATHER, st);
     hipLaunchKernelGGL(regather_kernel, dim3(regather_grid(s, bound)), dim3(kMoverThreads), 0, st,
-                       static_cast<const u32x4 *>(stage), static_cast<u32x4 *>(fin), p, s, u0, u1);
+                       static_cast<const u32x4 *>(stage), static_cast<u32x4 *>(fin), p, s, j0 * s.tp, j1 * s.tp);
     HIP_TRY(hipGetLastError());
     return MONTA_OK;
 }
 
-int launch_pack_regather(const Geometry &g, const PlanPtrs &p, const void *x, void *stage, void *fin, int slice,
-                         hipStream_t st)
+// packs slices [pj0, pj1) and regathers slices [rj0, rj1) in disjoint workgroups of one grid
+int launch_pack_regather(const Geometry &g, const PlanPtrs &p, const void *x, void *stage, void *fin, int pj0, int pj1,
+                         int rj0, int rj1, hipStream_t st)
 {
-    // packs `slice`, regathers `slice - 1`
     const Shape &s = g.s;
     const int per_slice = s.tp * s.Tu;
-    const int n_pack = mover_grid(s, per_slice);
-    const int n_reg = regather_grid(s, slice_rows_bound(g, 1));
+    const int n_pack = mover_grid(s, (pj1 - pj0) * per_slice);
+    const int n_reg = regather_grid(s, slice_rows_bound(g, rj1 - rj0));
     ProfScope ps(MONTA_K_PACK_REGATHER, st);
     hipLaunchKernelGGL(pack_regather_kernel, dim3(n_pack + n_reg), dim3(kMoverThreads), 0, st,
                        static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), static_cast<u32x4 *>(fin), p, s,
-                       slice * per_slice, per_slice, (slice - 1) * s.tp, slice * s.tp, n_pack);
+                       pj0 * per_slice, (pj1 - pj0) * per_slice, rj0 * s.tp, rj1 * s.tp, n_pack);
     HIP_TRY(hipGetLastError());
     return MONTA_OK;
 }
@@ -610,16 +607,54 @@ int launch_expert_layer(const monta_cfg *cfg, const Geometry &g, const void *x_f
     return MONTA_OK;
 }
 
-// The pipeline realisation one call uses: the caller's choice, or (-1) picked from what one slice moves.
-// Measured on MI355X: a co-scheduled launch (pack of slice j and regather of slice j-1 in one grid) saves a
-// launch boundary per slice, which decides it while a slice's copies take a few tens of microseconds; once they
-// take hundreds, two plain kernels run faster than the mixed grid (the regather alone reaches 6.6-7.0 TB/s, the
-// mixed grid 6.2-6.7) and the boundary no longer matters.
-int effective_pipeline_mode(const Geometry &g)
+// How one call runs the slice pipeline: the realisation (0, 1 or 2) and how many consecutive slices one launch
+// covers.  An explicit mode keeps one slice per launch.  The default (-1) chooses from the sizes, as the paper's
+// planner chooses its chunk count from the traffic (section "Network-traffic-aware"): measured on MI355X,
+//  - a launch boundary costs a few microseconds of idle memory system, so slices that move only tens of
+//    megabytes are grouped until a launch's share of STAGE reaches 256 MiB (the size of the memory-side cache:
+//    what the pack writes is still there when the regather reads it); a problem that fits one group runs as
+//    plan + pack of everything, then one regather;
+//  - co-scheduling pack(j) with regather(j-1) in one grid saves a boundary per slice, which decides it while
+//    a group's copies take a few tens of microseconds; once they take hundreds, two plain kernels run faster
+//    than the mixed grid (the regather alone reaches 6.6-7.0 TB/s, the mixed grid 6.2-6.7).
+struct PipePlan {
+    int mode;
+    int first;      // slices in the first launch group
+    int spg;        // slices in every later group
+};
+
+// Can the kernel that finishes the plan also pack (plan_pack_kernel)?  It needs a histogram table small enough to
+// rebuild in every pack workgroup and token groups that never straddle two route workgroups.
+bool plan_pack_shape_ok(const Geometry &g)
 {
-    if (g.modes.pipeline >= 0) return g.modes.pipeline;
-    const int64_t slice_bytes = slice_rows_bound(g, 1) * g.row_bytes;      // rows one slice may put into STAGE
-    return slice_bytes >= kSerialSliceBytes ? 2 : 1;
+    const Shape &s = g.s;
+    const int rows_per_wg = kMoverThreads / s.lpr;
+    return s.fast_plan && (int64_t)s.num_blocks * s.E <= 2048 && s.Tu % s.TB == 0 && rows_per_wg <= s.TB &&
+           kMoverThreads >= s.TB;
+}
+
+PipePlan pipeline_plan(const Geometry &g)
+{
+    if (g.modes.pipeline >= 0) return {g.modes.pipeline, 1, 1};
+    const int S = g.s.S;
+    const int64_t slice_bytes = slice_rows_bound(g, 1) * g.row_bytes;      // what one slice may put into STAGE
+    if (slice_bytes >= kGroupBytes) return {2, 1, 1};
+    int spg = (int)(kGroupBytes / slice_bytes);
+    if (spg > S) spg = S;
+    int groups = (S + spg - 1) / spg;
+    spg = (S + groups - 1) / groups;                                       // even groups
+    if (groups > 1) return {spg * slice_bytes >= kGroupBytes * 3 / 4 ? 2 : 1, spg, spg};
+    // Everything fits one group.  The pack workgroups of the fused plan-and-pack kernel each rebuild the plan's
+    // scans before their first store; with one round of them resident on the chip that hides behind the row
+    // reads, with several rounds it is paid every round (measured: 8192 of them pack 192 MiB at 5.0 TB/s, the
+    // plain pack at 6.3).  So the first launch takes about one round of workgroups (whole slices), the rest
+    // of the slices form the second group: plan + pack(first), pack(rest) with regather(first), regather(rest).
+    if (!plan_pack_shape_ok(g) || S == 1) return {1, S, S};
+    const int64_t round_tokens = (int64_t)kResidentMoverWgs * (kMoverThreads / g.s.lpr);
+    int first = (int)(round_tokens / ((int64_t)g.s.tp * g.s.Tu));
+    if (first < 1) first = 1;
+    if (first >= S) first = S - 1;
+    return {1, first, S - first};
 }
 
 int route_impl(const Geometry &g, const float *logits, int32_t *topk_idx, float *gates, void *ws, hipStream_t st)
@@ -636,38 +671,46 @@ int route_impl(const Geometry &g, const float *logits, int32_t *topk_idx, float 
     return MONTA_OK;
 }
 
-int dispatch_regather_impl(const Geometry &g, const void *x, void *stage, void *final_, const void *ws, hipStream_t st)
+// the pipeline from group `first` on (group 0 may have been packed already by the kernel that finishes the plan)
+int pipeline_impl(const Geometry &g, const PipePlan &pp, const void *x, void *stage, void *final_, const void *ws,
+                  bool group0_packed, hipStream_t st)
 {
     int rc = MONTA_OK;
     const PlanPtrs p = plan_ptrs(g, ws);
     const int S = g.s.S;
-    const int mode = effective_pipeline_mode(g);
-    if (mode == 2) {
-        for (int j = 0; j < S; ++j) {
-            if ((rc = launch_pack(g, p, x, stage, j, st))) return rc;
-            if ((rc = launch_regather(g, p, stage, final_, j, st))) return rc;
+    const int first = pp.first < S ? pp.first : S, spg = pp.spg;
+    auto lo = [&](int gi) { return gi == 0 ? 0 : first + (gi - 1) * spg; };
+    auto hi = [&](int gi) { const int h = first + gi * spg; return h < S ? h : S; };
+    const int G = 1 + (S - first + spg - 1) / spg;
+    if (pp.mode == 2) {
+        for (int gi = 0; gi < G; ++gi) {
+            if (!(gi == 0 && group0_packed))
+                if ((rc = launch_pack(g, p, x, stage, lo(gi), hi(gi), st))) return rc;
+            if ((rc = launch_regather(g, p, stage, final_, lo(gi), hi(gi), st))) return rc;
         }
         return MONTA_OK;
     }
-    if (mode == 1) {
-        if ((rc = launch_pack(g, p, x, stage, 0, st))) return rc;
-        for (int j = 1; j < S; ++j)
-            if ((rc = launch_pack_regather(g, p, x, stage, final_, j, st))) return rc;
-        return launch_regather(g, p, stage, final_, S - 1, st);
+    if (pp.mode == 1) {
+        if (!group0_packed)
+            if ((rc = launch_pack(g, p, x, stage, lo(0), hi(0), st))) return rc;
+        for (int gi = 1; gi < G; ++gi)
+            if ((rc = launch_pack_regather(g, p, x, stage, final_, lo(gi), hi(gi), lo(gi - 1), hi(gi - 1), st))) return rc;
+        return launch_regather(g, p, stage, final_, lo(G - 1), hi(G - 1), st);
     }
     // mode 0: packs on the caller's stream, regathers on the side stream, one event per slice.  The side stream
     // and its events are shared by every caller on this device: the whole enqueue holds the device's lock, so
     // that each wait pairs with the record made just before it (a wait refers to the event's latest record at
     // the time the wait is enqueued; what another call records later does not change it).
     DevState *d = nullptr;
-    if ((rc = dev_state(S, &d))) return rc;
+    if ((rc = dev_state(G, &d))) return rc;
     std::lock_guard<std::mutex> lk(d->mu);
-    for (int j = 0; j < S; ++j) {
-        if ((rc = launch_pack(g, p, x, stage, j, st))) return rc;
-        HIP_TRY(hipEventRecord(d->ev[j], st));
-        HIP_TRY(hipStreamWaitEvent(d->side, d->ev[j], 0));
+    for (int gi = 0; gi < G; ++gi) {
+        if (!(gi == 0 && group0_packed))
+            if ((rc = launch_pack(g, p, x, stage, lo(gi), hi(gi), st))) return rc;
+        HIP_TRY(hipEventRecord(d->ev[gi], st));
+        HIP_TRY(hipStreamWaitEvent(d->side, d->ev[gi], 0));
         prof_break_chain(d->side);
-        if ((rc = launch_regather(g, p, stage, final_, j, d->side))) return rc;
+        if ((rc = launch_regather(g, p, stage, final_, lo(gi), hi(gi), d->side))) return rc;
     }
     HIP_TRY(hipEventRecord(d->done, d->side));
     HIP_TRY(hipStreamWaitEvent(st, d->done, 0));
@@ -675,34 +718,40 @@ int dispatch_regather_impl(const Geometry &g, const void *x, void *stage, void *
     return MONTA_OK;
 }
 
+int dispatch_regather_impl(const Geometry &g, const void *x, void *stage, void *final_, const void *ws, hipStream_t st)
+{
+    return pipeline_impl(g, pipeline_plan(g), x, stage, final_, ws, false, st);
+}
+
+// Does monta_route_dispatch_regather finish the plan and pack the first launch group in one grid?  An explicit
+// mode 0 or 2 keeps the plain sequence of kernels.
+bool plan_pack_fused(const Geometry &g, const PipePlan &pp)
+{
+    return pp.mode != 0 && (pp.mode == 1 || g.modes.pipeline < 0) && plan_pack_shape_ok(g);
+}
+
 int route_dispatch_regather_impl(const Geometry &g, const float *logits, const void *x, int32_t *topk_idx, float *gates,
                                  void *stage, void *final_, void *ws, hipStream_t st)
 {
     int rc = MONTA_OK;
     const Shape &s = g.s;
+    const PipePlan pp = pipeline_plan(g);
     const int rows_per_wg = kMoverThreads / s.lpr;
-    // The overlapped form needs a histogram table small enough to rebuild in every pack workgroup and
-    // token groups that never straddle two route workgroups.
-    const bool overlap = effective_pipeline_mode(g) == 1 && s.fast_plan && (int64_t)s.num_blocks * s.E <= 2048 &&
-                         s.Tu % s.TB == 0 && rows_per_wg <= s.TB && kMoverThreads >= s.TB;
-    if (!overlap) {
+    if (!plan_pack_fused(g, pp)) {
         if ((rc = route_impl(g, logits, topk_idx, gates, ws, st))) return rc;
-        return dispatch_regather_impl(g, x, stage, final_, ws, st);
+        return pipeline_impl(g, pp, x, stage, final_, ws, false, st);
     }
     PlanPtrs p = plan_ptrs(g, ws);
     if ((rc = launch_route(g, p, logits, topk_idx, gates, st))) return rc;
     {
-        const int per_slice = s.tp * s.Tu;
-        const int n_pack = (per_slice + rows_per_wg - 1) / rows_per_wg;     // one token group per workgroup, no striding
+        const int nt = (pp.first < s.S ? pp.first : s.S) * s.tp * s.Tu;      // tokens of the first group
+        const int n_pack = (nt + rows_per_wg - 1) / rows_per_wg;           // one token group per workgroup, no striding
         ProfScope ps(MONTA_K_PLAN_PACK, st);
         hipLaunchKernelGGL(plan_pack_kernel, dim3(s.num_blocks + n_pack), dim3(kMoverThreads), 0, st, topk_idx,
-                           static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), p, s, 0, per_slice,
-                           s.num_blocks);
+                           static_cast<const u32x4 *>(x), static_cast<u32x4 *>(stage), p, s, 0, nt, s.num_blocks);
         HIP_TRY(hipGetLastError());
     }
-    for (int j = 1; j < s.S; ++j)
-        if ((rc = launch_pack_regather(g, p, x, stage, final_, j, st))) return rc;
-    return launch_regather(g, p, stage, final_, s.S - 1, st);
+    return pipeline_impl(g, pp, x, stage, final_, ws, true, st);
 }
 
 int combine_impl(const Geometry &g, int dtype, const void *y, const float *gates, void *out, const void *ws, hipStream_t st)
@@ -711,7 +760,7 @@ int combine_impl(const Geometry &g, int dtype, const void *y, const float *gates
     const PlanPtrs p = plan_ptrs(g, ws);
     ProfScope ps(MONTA_K_COMBINE, st);
     const dim3 grid(mover_grid(s, s.T)), block(kMoverThreads);
-    const bool wide = s.vpr > kCombineWideVpr;   // rows above 8 KiB: 4 vectors per lane cover 16 KiB in one pass
+    const bool wide = s.vpr > 2 * s.lpr;   // more than two vectors per lane: 4 per pass
     const u32x4 *yv = static_cast<const u32x4 *>(y);
     u32x4 *ov = static_cast<u32x4 *>(out);
     // With three or more choices per token the software-pipelined form wins (measured on MI355X, 65536 tokens of
@@ -860,10 +909,10 @@ int monta_route_dispatch_expert(const monta_cfg *cfg, const float *logits, const
     std::lock_guard<std::mutex> lk(d->mu);      // the side stream and its events are shared per device
     if ((rc = route_impl(g, logits, topk_idx, gates, ws, st))) return rc;
     const PlanPtrs p = plan_ptrs(g, ws);
-    if ((rc = launch_pack(g, p, x, stage, 0, st))) return rc;
+    if ((rc = launch_pack(g, p, x, stage, 0, 1, st))) return rc;
     for (int j = 0; j < S; ++j) {
-        rc = j + 1 < S ? launch_pack_regather(g, p, x, stage, final_, j + 1, st)      // pack(j+1) and regather(j)
-                       : launch_regather(g, p, stage, final_, j, st);
+        rc = j + 1 < S ? launch_pack_regather(g, p, x, stage, final_, j + 1, j + 2, j, j + 1, st)      // pack(j+1) and regather(j)
+                       : launch_regather(g, p, stage, final_, j, j + 1, st);
         if (rc) return rc;
         HIP_TRY(hipEventRecord(d->ev[j], st));
         HIP_TRY(hipStreamWaitEvent(d->side, d->ev[j], 0));
@@ -906,7 +955,8 @@ int monta_dispatch(const monta_cfg *cfg, const void *x, void *stage, const void 
     if (slice < -1 || slice >= cfg->slices) return MONTA_ERR_INVALID;
     if ((rc = check_act_ptrs(x, stage))) return rc;
     if ((rc = check_ws(ws))) return rc;
-    return launch_pack(g, plan_ptrs(g, ws), x, stage, slice, static_cast<hipStream_t>(stream));
+    return launch_pack(g, plan_ptrs(g, ws), x, stage, slice < 0 ? 0 : slice, slice < 0 ? g.s.S : slice + 1,
+                       static_cast<hipStream_t>(stream));
 }
 
 int monta_regather(const monta_cfg *cfg, const void *stage, void *final_, const void *ws, int slice, void *stream)
@@ -918,7 +968,8 @@ int monta_regather(const monta_cfg *cfg, const void *stage, void *final_, const 
     if ((rc = check_act_ptrs(stage, final_))) return rc;
     if (stage == final_) return MONTA_ERR_INVALID;
     if ((rc = check_ws(ws))) return rc;
-    return launch_regather(g, plan_ptrs(g, ws), stage, final_, slice, static_cast<hipStream_t>(stream));
+    return launch_regather(g, plan_ptrs(g, ws), stage, final_, slice < 0 ? 0 : slice, slice < 0 ? g.s.S : slice + 1,
+                           static_cast<hipStream_t>(stream));
 }
 
 int monta_dispatch_regather(const monta_cfg *cfg, const void *x, void *stage, void *final_, const void *ws,
@@ -1008,7 +1059,7 @@ int launch_unregather_combine(const Geometry &g, const PlanPtrs &p, int dtype, c
     const int n_unreg = u0 < u1 ? regather_grid(s, slice_rows_bound(g, (u1 - u0) / s.tp)) : 0;
     const int n_comb = nt > 0 ? mover_grid(s, nt) : 0;
     if (n_unreg + n_comb == 0) return MONTA_OK;
-    const bool wide = s.vpr > kCombineWideVpr;
+    const bool wide = s.vpr > 2 * s.lpr;
     const u32x4 *yv = static_cast<const u32x4 *>(y);
     u32x4 *sv = static_cast<u32x4 *>(y_stage), *ov = static_cast<u32x4 *>(out);
     const dim3 grid(n_unreg + n_comb), block(kMoverThreads);
@@ -1123,7 +1174,7 @@ int monta_route_dispatch_combine_static(const monta_cfg *cfg, const float *logit
     // event profiling creates events per launch and the two-stream pipeline creates a stream: neither belongs
     // in a call that must not allocate
     if (g_prof_on.load()) return MONTA_ERR_INVALID;
-    if (g.modes.pipeline == 0) g.modes.pipeline = -1;
+    if (g.modes.pipeline == 0) g.modes.pipeline = -1;      // pipeline_plan() then never answers 0
     void *ws = nullptr;
     if ((rc = static_scratch(&ws))) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -1132,6 +1183,21 @@ int monta_route_dispatch_combine_static(const monta_cfg *cfg, const float *logit
     HIP_TRY(hipGetLastError());
     if ((rc = route_dispatch_regather_impl(g, logits, x, topk_idx, gates, stage, final_, ws, st))) return rc;
     return combine_impl(g, cfg->dtype, final_, gates, out, ws, st);
+}
+
+int monta_pipeline_query(const monta_cfg *cfg, int32_t *mode, int32_t *first_slices, int32_t *slices_per_launch,
+                         int32_t *plan_fused)
+{
+    if (!mode || !first_slices || !slices_per_launch || !plan_fused) return MONTA_ERR_NULL;
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    const PipePlan pp = pipeline_plan(g);
+    *mode = pp.mode;
+    *first_slices = pp.first < g.s.S ? pp.first : g.s.S;
+    *slices_per_launch = pp.spg;
+    *plan_fused = plan_pack_fused(g, pp) ? 1 : 0;
+    return MONTA_OK;
 }
 
 int monta_set_pipeline_mode(int mode)

@@ -203,11 +203,12 @@ __global__ __launch_bounds__(1024) void route_plan_kernel(const float *__restric
     // lane of the workgroup has an exp to do, not only one lane per token; then the denominator is summed in j
     // order (or taken from the sum over all experts), one division, one rounding to fp32.
     const int npairs = nt * k;
-    for (int idx = tid; idx < npairs; idx += blockDim.x) {
-        const int tk = idx / k, j = idx - tk * k;
+    for (int tk = tid; tk < nt; tk += blockDim.x) s_w[tk * k] = 1.0;
+    for (int idx = tid; idx < nt * (k - 1); idx += blockDim.x) {         // only the choices j >= 1 need an exp
+        const int tk = idx / (k - 1), j = 1 + idx - tk * (k - 1);
         const float *row = s_l + tk * stride;
         const int *sel = s_sel + tk * k;
-        s_w[idx] = j == 0 ? 1.0 : exp((double)row[sel[j]] - (double)row[sel[0]]);
+        s_w[tk * k + j] = exp((double)row[sel[j]] - (double)row[sel[0]]);
     }
     __syncthreads();
     for (int idx = tid; idx < npairs; idx += blockDim.x) {

@@ -192,3 +192,23 @@ def test_static_scratch_entry_point_refuses_oversized_problems_on_the_host():
     assert rc == -6 and "static" in m.monta_strerror(rc)
     # argument checks come first
     assert lib.monta_route_dispatch_combine_static(ctypes.byref(cfg), None, fake, fake, fake, fake, fake, fake, None) == -3
+
+
+def test_pipeline_query_reports_the_launch_grouping():
+    """Host-only: small problems run in three launches (first slice with the plan, the rest as one group),
+    slices of 256 MiB and more run one by one as two kernels each, an explicit mode keeps one slice per launch."""
+    import workloads
+    def q(name, **kw):
+        w = workloads.CONFIGS[name].with_(**kw)
+        return m.monta_pipeline_query(m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices,
+                                                 w.capacity_factor, w.renorm, w.padded))
+    assert m.monta_get_pipeline_mode() == -1
+    assert q("mixtral") == (1, 1, 3, True)
+    assert q("2x70b") == (1, 1, 3, True)
+    assert q("longctx") == (2, 1, 1, True)
+    assert q("longctx", slices=8) == (2, 2, 2, True)
+    assert q("skewed") == (2, 1, 1, False)
+    for mode in (0, 1, 2):
+        m.monta_set_pipeline_mode(mode)
+        assert q("mixtral") == (mode, 1, 1, mode == 1)
+    m.monta_set_pipeline_mode(-1)

@@ -433,7 +433,7 @@ def test_hip_graph_replays_match_eager(m):
     from paper_2411_00662_amd import buffers as bufs
     w = Workload("graph", 4096, 1024, BF16, 8, 2, 4, 2, 4, 0.8, zipf_s=0.6)
     cfg = cfg_of(m, w)
-    m.monta_set_pipeline_mode(1)
+    m.monta_set_pipeline_mode(-1)        # the default: launch groups chosen by size (three launches here)
     inputs = [workloads.make_inputs(w, seed=s) for s in (1, 2, 3)]
     b = m.alloc_buffers(cfg, *inputs[0], canary=0)
     stream = torch.cuda.Stream()
@@ -502,7 +502,7 @@ def test_random_small_shapes(m):
         renorm = int(rng.integers(0, 2))
         w = Workload("rand", T, H, dtype, E, k, ep, tp, S, cf, renorm=renorm, zipf_s=float(rng.choice([0.0, 0.7])))
         logits, x = workloads.make_inputs(w, seed=1000 + done)
-        mode = int(rng.integers(0, 3))
+        mode = int(rng.integers(-1, 3))          # -1: the size-chosen launch grouping
         how = str(rng.choice(["pipeline", "all", "slices_reversed", "fused_call"]))
         plan_mode = int(rng.choice([-1, 0]))
         cache = int(rng.integers(-1, 64))
