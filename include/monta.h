@@ -203,6 +203,20 @@ int monta_regather(const monta_cfg *cfg, const void *stage, void *final_, const 
  * two-pass order against it. */
 int monta_allgather(const monta_cfg *cfg, const void *stage, void *gathered, const void *ws, int slice, void *stream);
 
+/* The two-pass order with the paper's third transform (paragraph "AllGather and D2D copy Pipelining", Fig. 8;
+ * the stream picture of section "AllToAll performance", Implementation): for every chunk j the gather
+ * (STAGE rows of slice j -> gathered) and then the D2D copy to index offsets (gathered -> FINAL), with the
+ * copy of chunk j overlapping the gather of chunk j+1.  stage must hold every slice (after monta_dispatch).
+ * schedule 0: chunk by chunk, gather then copy, nothing overlaps (the O2 order on one stream);
+ *          1: S+1 launches on `stream`; launch j gathers chunk j and, in disjoint workgroups of the same
+ *             grid, copies chunk j-1;
+ *          2: gathers on `stream`, copies on the library's side stream (default priority), one event per
+ *             chunk, joined back into `stream` before the call returns.
+ * gathered [max_rows][H] ends up equal to stage below R; final_ equals what monta_regather produces.
+ * MONTA_ERR_INVALID for another schedule or aliased buffers. */
+int monta_allgather_regather(const monta_cfg *cfg, const void *stage, void *gathered, void *final_, const void *ws,
+                             int schedule, void *stream);
+
 /* The slice pipeline (the paper's multi-stream schedule, section "AllToAll
  * performance", Implementation): regather(j) runs after pack(j) and overlaps
  * pack(j+1); everything has finished, in stream order, when the call's work on
@@ -333,7 +347,8 @@ enum monta_kernel_id {
     MONTA_K_ALLGATHER = 10,
     MONTA_K_GATE = 11,      /* gate projection                                */
     MONTA_K_EXPERT = 12,    /* expert layer (grouped GEMM)                    */
-    MONTA_K_COUNT = 13
+    MONTA_K_ALLGATHER_REGATHER = 13, /* co-scheduled grid of the pipelined two-pass order */
+    MONTA_K_COUNT = 14
 };
 int monta_profile_enable(int on);
 int monta_profile_reset(void);

@@ -19,7 +19,7 @@ FP32, BF16 = 0, 1
 (K_ROUTE, K_POSITIONS, K_PACK, K_REGATHER, K_PACK_REGATHER, K_COMBINE, K_COPY, K_PLAN_PACK, K_UNREGATHER,
  K_UNREGATHER_COMBINE, K_ALLGATHER, K_GATE, K_EXPERT) = range(13)
 KERNEL_NAMES = ["route_plan", "positions", "pack", "regather", "pack_regather", "combine", "copy", "plan_pack",
-                "unregather", "unregather_combine", "allgather", "gate", "expert"]
+                "unregather", "unregather_combine", "allgather", "gate", "expert", "allgather_regather"]
 
 
 class MontaError(RuntimeError):
@@ -73,7 +73,7 @@ EXPORTS = ["monta_workspace_bytes", "monta_ws_layout_query", "monta_ws_init", "m
            "monta_unregather_combine", "monta_allgather", "monta_set_pipeline_mode",
            "monta_get_pipeline_mode", "monta_set_plan_mode", "monta_get_plan_mode", "monta_set_cache_policy", "monta_get_cache_policy", "monta_copy", "monta_profile_enable", "monta_profile_reset",
            "monta_profile_read", "monta_plan_chunk_times", "monta_plan_strategy", "monta_strerror",
-           "monta_last_hip_error", "monta_shutdown", "monta_route_dispatch_combine_static", "monta_pipeline_query"]
+           "monta_last_hip_error", "monta_shutdown", "monta_route_dispatch_combine_static", "monta_pipeline_query", "monta_allgather_regather"]
 
 _lib = None
 
@@ -98,6 +98,7 @@ def lib() -> ctypes.CDLL:
         L.monta_route_dispatch_regather.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.monta_unregather.argtypes = [cfgp, vp, vp, vp, i32, vp]
         L.monta_allgather.argtypes = [cfgp, vp, vp, vp, i32, vp]
+        L.monta_allgather_regather.argtypes = [cfgp, vp, vp, vp, vp, i32, vp]
         L.monta_combine_staged.argtypes = [cfgp, vp, vp, vp, vp, i32, vp]
         L.monta_unregather_combine.argtypes = [cfgp, vp, vp, vp, vp, vp, vp]
         L.monta_set_pipeline_mode.argtypes = [i32]
@@ -248,6 +249,14 @@ def monta_route_dispatch_combine_static(cfg, logits, x, topk_idx, gates, stage, 
         ctypes.byref(cfg), _ptr(logits, T * E * 4, "logits"), _ptr(x, T * row, "x"), _ptr(topk_idx, T * k * 4, "topk_idx"),
         _ptr(gates, T * k * 4, "gates"), _ptr(stage, L.max_rows * row, "stage"), _ptr(final_, L.max_rows * row, "final_"),
         _ptr(out, T * row, "out"), _stream(stream)), "monta_route_dispatch_combine_static")
+
+
+def monta_allgather_regather(cfg, stage, gathered, final_, ws, schedule=1, stream=None):
+    L = monta_ws_layout_query(cfg)
+    row = cfg.hidden * _bpe(cfg)
+    _check(lib().monta_allgather_regather(ctypes.byref(cfg), _ptr(stage, L.max_rows * row, "stage"),
+                                          _ptr(gathered, L.max_rows * row, "gathered"), _ptr(final_, L.max_rows * row, "final_"),
+                                          _ptr(ws, L.ws_bytes, "ws"), int(schedule), _stream(stream)), "monta_allgather_regather")
 
 
 def monta_combine(cfg, y, gates, out, ws, stream=None):

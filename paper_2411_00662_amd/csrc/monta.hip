@@ -998,6 +998,29 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
     return combine_impl(g, cfg->dtype, y, gates, out, ws, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+
+int allgather_grid(const Geometry &g, int nslices)
+{
+    const int64_t vecs = slice_rows_bound(g, nslices) * g.s.vpr;
+    int64_t wg = (vecs + (int64_t)kMoverThreads * kVecInFlight - 1) / ((int64_t)kMoverThreads * kVecInFlight);
+    if (wg < 1) wg = 1;
+    if (wg > 32768) wg = 32768;
+    return (int)wg;
+}
+
+int launch_allgather(const Geometry &g, const PlanPtrs &p, const void *stage, void *gathered, int j0, int j1, hipStream_t st)
+{
+    const Shape &s = g.s;
+    ProfScope ps(MONTA_K_ALLGATHER, st);
+    hipLaunchKernelGGL(allgather_kernel, dim3((unsigned)allgather_grid(g, j1 - j0)), dim3(kMoverThreads), 0, st,
+                       static_cast<const u32x4 *>(stage), static_cast<u32x4 *>(gathered), p, s, j0 * s.tp, j1 * s.tp);
+    HIP_TRY(hipGetLastError());
+    return MONTA_OK;
+}
+
+}  // namespace
+
 int monta_allgather(const monta_cfg *cfg, const void *stage, void *gathered, const void *ws, int slice, void *stream)
 {
     Geometry g;
@@ -1007,19 +1030,59 @@ int monta_allgather(const monta_cfg *cfg, const void *stage, void *gathered, con
     if ((rc = check_act_ptrs(stage, gathered))) return rc;
     if (stage == gathered) return MONTA_ERR_INVALID;
     if ((rc = check_ws(ws))) return rc;
+    return launch_allgather(g, plan_ptrs(g, ws), stage, gathered, slice < 0 ? 0 : slice, slice < 0 ? g.s.S : slice + 1,
+                            static_cast<hipStream_t>(stream));
+}
+
+int monta_allgather_regather(const monta_cfg *cfg, const void *stage, void *gathered, void *final_, const void *ws,
+                             int schedule, void *stream)
+{
+    Geometry g;
+    int rc = validate(cfg, &g);
+    if (rc) return rc;
+    if (schedule < 0 || schedule > 2) return MONTA_ERR_INVALID;
+    if ((rc = check_act_ptrs(stage, gathered))) return rc;
+    if ((rc = check_act_ptrs(gathered, final_))) return rc;
+    if (stage == gathered || gathered == final_ || stage == final_) return MONTA_ERR_INVALID;
+    if ((rc = check_ws(ws))) return rc;
     const Shape &s = g.s;
     const PlanPtrs p = plan_ptrs(g, ws);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int u0 = slice < 0 ? 0 : slice * s.tp;
-    const int u1 = slice < 0 ? s.U : (slice + 1) * s.tp;
-    const int64_t vecs = slice_rows_bound(g, slice < 0 ? s.S : 1) * s.vpr;
-    int64_t wg = (vecs + (int64_t)kMoverThreads * kVecInFlight - 1) / ((int64_t)kMoverThreads * kVecInFlight);
-    if (wg < 1) wg = 1;
-    if (wg > 32768) wg = 32768;
-    ProfScope ps(MONTA_K_ALLGATHER, st);
-    hipLaunchKernelGGL(allgather_kernel, dim3((unsigned)wg), dim3(kMoverThreads), 0, st,
-                       static_cast<const u32x4 *>(stage), static_cast<u32x4 *>(gathered), p, s, u0, u1);
-    HIP_TRY(hipGetLastError());
+    const int S = s.S;
+    if (schedule == 0) {            // chunk by chunk, gather then copy: no overlap
+        for (int j = 0; j < S; ++j) {
+            if ((rc = launch_allgather(g, p, stage, gathered, j, j + 1, st))) return rc;
+            if ((rc = launch_regather(g, p, gathered, final_, j, j + 1, st))) return rc;
+        }
+        return MONTA_OK;
+    }
+    if (schedule == 1) {            // launch j gathers chunk j and, in disjoint workgroups, copies chunk j-1
+        if ((rc = launch_allgather(g, p, stage, gathered, 0, 1, st))) return rc;
+        for (int j = 1; j < S; ++j) {
+            const int n_gather = allgather_grid(g, 1), n_copy = regather_grid(s, slice_rows_bound(g, 1));
+            ProfScope ps(MONTA_K_ALLGATHER_REGATHER, st);
+            hipLaunchKernelGGL(allgather_regather_kernel, dim3(n_gather + n_copy), dim3(kMoverThreads), 0, st,
+                               static_cast<const u32x4 *>(stage), static_cast<u32x4 *>(gathered), static_cast<u32x4 *>(final_),
+                               p, s, j * s.tp, (j + 1) * s.tp, (j - 1) * s.tp, j * s.tp, n_gather);
+            HIP_TRY(hipGetLastError());
+        }
+        return launch_regather(g, p, gathered, final_, S - 1, S, st);
+    }
+    // schedule 2: the paper's stream picture: gathers on the caller's stream, copies on the library's side stream
+    // (default priority), one event per chunk, joined back into the caller's stream
+    DevState *d = nullptr;
+    if ((rc = dev_state(S, &d))) return rc;
+    std::lock_guard<std::mutex> lk(d->mu);
+    for (int j = 0; j < S; ++j) {
+        if ((rc = launch_allgather(g, p, stage, gathered, j, j + 1, st))) return rc;
+        HIP_TRY(hipEventRecord(d->ev[j], st));
+        HIP_TRY(hipStreamWaitEvent(d->side, d->ev[j], 0));
+        prof_break_chain(d->side);
+        if ((rc = launch_regather(g, p, gathered, final_, j, j + 1, d->side))) return rc;
+    }
+    HIP_TRY(hipEventRecord(d->done, d->side));
+    HIP_TRY(hipStreamWaitEvent(st, d->done, 0));
+    prof_break_chain(st);
     return MONTA_OK;
 }
 

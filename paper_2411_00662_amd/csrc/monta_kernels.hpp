@@ -1104,17 +1104,16 @@ __global__ __launch_bounds__(kMoverThreads) void combine_kernel(const u32x4 *__r
 
 // The gather as a pass of its own: the STAGE rows of units [u0, u1) (one contiguous range, read from the
 // device table) copied unchanged into a second buffer.
-__global__ __launch_bounds__(kMoverThreads) void allgather_kernel(const u32x4 *__restrict__ stage,
-                                                                  u32x4 *__restrict__ gathered, PlanPtrs p, Shape s,
-                                                                  int u0, int u1)
+__device__ __forceinline__ void allgather_rows(const u32x4 *__restrict__ stage, u32x4 *__restrict__ gathered,
+                                               const PlanPtrs &p, const Shape &s, int u0, int u1, int wg, int nwg)
 {
     int r0 = p.unit_rows[u0], r1 = p.unit_rows[u1];
     if (r0 < 0) r0 = 0;
     if (r1 > s.max_rows) r1 = s.max_rows;
     if (r1 <= r0) return;
     const size_t first = (size_t)r0 * s.vpr, nvec = (size_t)(r1 - r0) * s.vpr;
-    const size_t stride = (size_t)gridDim.x * kMoverThreads * kVecInFlight;
-    for (size_t base = (size_t)blockIdx.x * kMoverThreads * kVecInFlight + threadIdx.x; base < nvec; base += stride) {
+    const size_t stride = (size_t)nwg * kMoverThreads * kVecInFlight;
+    for (size_t base = (size_t)wg * kMoverThreads * kVecInFlight + threadIdx.x; base < nvec; base += stride) {
         u32x4 val[kVecInFlight];
 #pragma unroll
         for (int q = 0; q < kVecInFlight; ++q)
@@ -1122,6 +1121,43 @@ __global__ __launch_bounds__(kMoverThreads) void allgather_kernel(const u32x4 *_
 #pragma unroll
         for (int q = 0; q < kVecInFlight; ++q)
             if (base + (size_t)q * kMoverThreads < nvec) st16<false>(gathered + first + base + (size_t)q * kMoverThreads, val[q]);
+    }
+}
+
+__global__ __launch_bounds__(kMoverThreads) void allgather_kernel(const u32x4 *__restrict__ stage,
+                                                                  u32x4 *__restrict__ gathered, PlanPtrs p, Shape s,
+                                                                  int u0, int u1)
+{
+    allgather_rows(stage, gathered, p, s, u0, u1, blockIdx.x, gridDim.x);
+}
+
+// The paper's third transform (paragraph "AllGather and D2D copy Pipelining", Fig. 8): while the D2D copy
+// places chunk j from the gathered buffer, the gather of chunk j+1 already runs.  One grid, two jobs in
+// disjoint, interleaved workgroups: the first n_gather_wg gather units [gu0, gu1) (STAGE -> gathered), the
+// others copy units [cu0, cu1) from `gathered` to their index offsets in FINAL.  The two ranges are different
+// chunks, so the jobs touch disjoint rows of `gathered`.
+__global__ __launch_bounds__(kMoverThreads) void allgather_regather_kernel(const u32x4 *__restrict__ stage,
+                                                                           u32x4 *gathered, u32x4 *__restrict__ fin,
+                                                                           PlanPtrs p, Shape s, int gu0, int gu1,
+                                                                           int cu0, int cu1, int n_gather_wg)
+{
+    const int n_copy_wg = gridDim.x - n_gather_wg;
+    const int bid = blockIdx.x;
+    const int pairs = n_gather_wg < n_copy_wg ? n_gather_wg : n_copy_wg;
+    bool is_gather;
+    int idx;
+    if (bid < 2 * pairs) {
+        is_gather = (bid & 1) == 0;
+        idx = bid >> 1;
+    } else {
+        is_gather = n_gather_wg > n_copy_wg;
+        idx = bid - pairs;
+    }
+    if (is_gather) {
+        allgather_rows(stage, gathered, p, s, gu0, gu1, idx, n_gather_wg);
+    } else {
+        regather_rows(gathered, fin, p, s, p.unit_rows[cu0], p.unit_rows[cu1], idx, n_copy_wg);
+        if (s.padded && cu0 == 0) pad_rows(fin, p, s, idx, n_copy_wg);
     }
 }
 

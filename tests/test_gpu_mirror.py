@@ -143,3 +143,43 @@ def test_two_pass_gather_then_copy(m):
         torch.cuda.synchronize()
         assert torch.equal(g2[:R].view(torch.int16 if w.dtype == BF16 else torch.int32),
                            b.stage[:R].view(torch.int16 if w.dtype == BF16 else torch.int32))
+
+
+@pytest.mark.parametrize("w", [Workload("g2", 1320, 264, BF16, 6, 3, 3, 5, 4, 0.7, zipf_s=0.8),
+                               Workload("g3", 900, 72, FP32, 5, 2, 5, 3, 1, 0.0),
+                               Workload("g4", 2048, 512, BF16, 8, 2, 4, 2, 4, 1.25, zipf_s=0.5, padded=1),
+                               workloads.CONFIGS["mixtral"], workloads.CONFIGS["2x70b"]], ids=lambda w: w.name)
+def test_pipelined_two_pass_gather_and_copy(m, w):
+    """The gather of chunk j+1 overlapping the D2D copy of chunk j (Fig. 8 order), in all three schedules:
+    `gathered` must equal the oracle's gathered buffer and FINAL the oracle's FINAL, canaries intact."""
+    import torch
+    from paper_2411_00662_amd import buffers as bufs
+    logits, x = workloads.make_inputs(w, seed=6)
+    ref = oracle.forward(logits, x, k=w.top_k, ep=w.ep, tp=w.tp, S=w.slices, cf=w.capacity_factor, padded=w.padded)
+    R = ref.plan.R
+    gathered_ref = oracle.allgather(ref.stage, ref.plan, w.tp, w.slices)
+    cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm, w.padded)
+    b = m.alloc_buffers(cfg, logits, x, canary=0xA5)
+    m.monta_route(cfg, b.logits, b.topk_idx, b.gates, b.ws)
+    m.monta_dispatch(cfg, b.x, b.stage, b.ws, -1)
+    rows_final = ref.plan.final_rows
+    for schedule in (0, 1, 2, 1):
+        print(f"pipelined two-pass {w.name} schedule={schedule}", flush=True)
+        gathered = torch.empty_like(b.stage)
+        gathered.view(torch.uint8).fill_(0xA5)
+        b.final.view(torch.uint8).fill_(0xA5)
+        m.monta_allgather_regather(cfg, b.stage, gathered, b.final, b.ws, schedule)
+        torch.cuda.synchronize()
+        gh = bufs.to_host_act(cfg, gathered)
+        np.testing.assert_array_equal(gh[:R], gathered_ref)
+        assert (gh[R:].view(np.uint8) == 0xA5).all()
+        fh = bufs.to_host_act(cfg, b.final)
+        if w.padded:
+            np.testing.assert_array_equal(fh[:rows_final], ref.final)
+        else:
+            np.testing.assert_array_equal(fh[:R], ref.final)
+        assert (fh[rows_final:].view(np.uint8) == 0xA5).all()
+    with pytest.raises(m.MontaError):
+        m.monta_allgather_regather(cfg, b.stage, b.stage, b.final, b.ws, 1)
+    with pytest.raises(m.MontaError):
+        m.monta_allgather_regather(cfg, b.stage, gathered, b.final, b.ws, 3)

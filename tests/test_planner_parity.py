@@ -84,3 +84,29 @@ def test_bad_inputs_are_rejected():
         m.monta_plan_strategy(bad)
     with pytest.raises(m.MontaError):
         m.monta_plan_chunk_times(pin, 0)
+
+
+def test_strategy_table_with_the_r3_curve_measured_on_mi355x():
+    """Algorithms 1-3 over Table 7's sequence lengths with this GPU's measured D2D-copy efficiency (the file
+    under profiles/ that r3_sweep wrote): the library against the Python reference, row by row."""
+    from paper_2411_00662_amd import plan_table as pt
+    r3 = pt.read_r3()
+    assert len(r3) >= 8 and all(0.0 < e <= 1.0 for _, e in r3) and r3 == sorted(r3)
+    rows = pt.plan_table(r3)
+    assert [r["seq"] for r in rows] == pt.SEQ_LENGTHS
+    for r in rows:
+        I = pt.traffic_of(r["seq"])
+        name, costs = P.select(I, 8, 2, 25e9, pt.R1, 200e9, pt.R2, 8e12, r3, 1e6, 64)
+        assert r["t_o1"] == pytest.approx(costs["O1"][1], rel=1e-12)
+        assert r["t_o2"] == pytest.approx(costs["O2"][1], rel=1e-12)
+        assert r["t_o3"] == pytest.approx(costs["O3"][1], rel=1e-12)
+        assert r["strategy"] == {"O1": 1, "O2": 2, "O3": 3}[name]
+        assert r["t_base"] == pytest.approx(P.t_base(I, 2, 25e9, pt.R1), rel=1e-12)
+        # every transform beats the plain AllToAll, and pipelining the copy too (O3) is never worse than O2
+        assert r["t_o3"] <= r["t_o2"] < r["t_o1"] < r["t_base"]
+    # at 8K the traffic is Table 8's 256 M (2^28 bytes under b*BPE = 4)
+    assert pt.traffic_of(8192) == 2 ** 28
+    # with the memory leg of this GPU the D2D copy of a 64 MiB chunk costs a twentieth of its gather
+    pin, keep = m.make_plan_in(pt.traffic_of(8192), 8, 2, 25e9, 200e9, 8e12, pt.R1, pt.R2, r3, 1e6, 64)
+    aa, ag, d2d = m.monta_plan_chunk_times(pin, 4)
+    assert d2d < ag / 10 and d2d == pytest.approx(2 ** 26 / (8e12 * P.lookup(r3, 2 ** 26)), rel=1e-12)
