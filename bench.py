@@ -229,7 +229,7 @@ def measure(args, w, steps, warmup, full):
             try:
                 entry = json.load(open(tpath)).get(f"{w.name}/S{w.slices}/mode{mode_label(mode)}", {})
                 for kname, v in entry.items():
-                    if kname.startswith(dom + "_kernel"):
+                    if kname.startswith(dom + "_kernel") or kname.startswith(dom + "_pf_kernel"):
                         traffic = v["total_bytes"]
             except (OSError, ValueError, KeyError):
                 traffic = None

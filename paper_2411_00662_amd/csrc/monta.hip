@@ -145,7 +145,7 @@ int validate(const monta_cfg *c, Geometry *g)
         const int pol = g->modes.cache;
         const int64_t touched = (2 * c->tokens + 2 * g->max_rows) * row;   // x + out + STAGE + FINAL
         if (pol >= 0) s.cache = pol;
-        else if (touched <= (384ll << 20)) s.cache = NT_REG_LD | NT_COMB_ST;
+        else if (touched <= (512ll << 20)) s.cache = NT_REG_LD | NT_COMB_LD | NT_COMB_ST;
         else if (touched <= (1024ll << 20)) s.cache = NT_REG_LD | NT_REG_ST | NT_COMB_LD | NT_COMB_ST;
         else s.cache = NT_PACK_LD | NT_REG_LD | NT_REG_ST | NT_COMB_LD | NT_COMB_ST;
     }
