@@ -327,6 +327,7 @@ def main():
     ap.add_argument("--config", default="skewed", help="tiny | mixtral | 2x70b | longctx | skewed (default: the largest)")
     ap.add_argument("--slices", type=int, default=0, help="override the workload's slice count")
     ap.add_argument("--mode", type=int, default=-1, help="pipeline realisation 0/1/2 (default -1: the library chooses)")
+    ap.add_argument("--plan-mode", type=int, default=-1, help="how the plan tables are built: -1 library default, 0 ticketed scan")
     ap.add_argument("--graph", type=int, default=0, help="replay the step from a captured HIP graph (1) or launch eagerly (0)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run the plain copy kernel on buffers of this size (profiler byte-counter calibration)")
@@ -367,6 +368,7 @@ def main():
     if args.padded:
         w = w.with_(padded=1)
     m.monta_set_pipeline_mode(args.mode)
+    m.monta_set_plan_mode(args.plan_mode)
 
     res = measure(args, w, args.steps, args.warmup, full=True)
     ms_per_step, ab = res["ms_per_step"], res["ab"]

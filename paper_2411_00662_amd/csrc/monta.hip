@@ -74,10 +74,19 @@ int64_t capacity_of(const monta_cfg *c)
     return (int64_t)v;
 }
 
+// lanes that share one token in the route kernel: each lane should still scan at least 8 experts
+int route_lanes_per_token(int TB, int E)
+{
+    int rl = 1;
+    while (rl < 8 && E / (2 * rl) >= 8 && TB * 2 * rl <= 1024) rl *= 2;
+    return rl;
+}
+
 size_t route_lds_bytes(int TB, int E, int k)
 {
     const int NW = TB > kWave ? TB / kWave : 1;
-    size_t b = ((size_t)TB * (E | 1) * 4 + (size_t)TB * k * 4 + 7) & ~(size_t)7;    // logits tile, selections
+    const int stride = route_row_stride(E, route_lanes_per_token(TB, E));
+    size_t b = ((size_t)TB * stride * 4 + (size_t)TB * k * 4 + 7) & ~(size_t)7;    // logits tile, selections
     return b + (size_t)E * NW * 8 + (size_t)TB * k * 8 + (size_t)TB * 8;            // bit masks, weights, denominators
 }
 
@@ -129,9 +138,7 @@ int validate(const monta_cfg *c, Geometry *g)
     s.fast_plan = (g->modes.plan != 0 && nb * s.E <= 65536) ? 1 : 0;
     g->route_lds = route_lds_bytes(TB, s.E, s.k);
     g->plan_threads = TB < kWave ? kWave : TB;
-    // lanes per token in the route kernel: each lane should still scan at least 8 experts
-    int rl = 1;
-    while (rl < 8 && s.E / (2 * rl) >= 8 && TB * 2 * rl <= 1024) rl *= 2;
+    const int rl = route_lanes_per_token(TB, s.E);
     s.rl = rl;
     g->route_threads = TB * rl < kWave ? kWave : TB * rl;
     const int64_t tk = c->tokens * (int64_t)c->top_k, ec = (int64_t)c->experts * s.C;

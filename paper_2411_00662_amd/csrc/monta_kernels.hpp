@@ -94,6 +94,12 @@ __device__ __forceinline__ void with_policy(bool ntl, bool nts, F f)
 
 // ------------------------------------------------------------ route + plan
 
+// Row stride (floats) of the logits tile in LDS.  A wave holds 64 / L tokens with L lanes each, lane (token, sub)
+// reads element sub + q * L of its row: with a stride that is L times an odd number the 64 lanes of a read hit 64
+// different banks (for L = 1 this is the usual odd stride).
+__host__ __device__ inline int route_row_stride(int E, int L) { return L * (((E + L - 1) / L) | 1); }
+
+
 // One workgroup routes TB consecutive tokens of ONE unit; s.rl lanes share a token (1 for few experts).
 //  1. the [nt][E] logits tile is staged in LDS (coalesced, odd row stride);
 //  2. k selection passes per token over its LDS row: the next winner is the largest
@@ -115,7 +121,7 @@ __global__ __launch_bounds__(1024) void route_plan_kernel(const float *__restric
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int E = s.E, k = s.k, TB = s.TB;
-    const int stride = E | 1;
+    const int stride = route_row_stride(E, s.rl);
     const int NW = TB > kWave ? TB / kWave : 1;
     float *s_l = reinterpret_cast<float *>(smem);
     int *s_sel = reinterpret_cast<int *>(s_l + (size_t)TB * stride);
@@ -378,6 +384,7 @@ struct BlockPlan {
     int sbefore[256];  // pairs of e in slices before b's slice
     int sin[256];      // pairs of e in b's slice
     int forder[256];   // index of block (u, e)'s first row when the slice's rows are listed expert by expert
+    int alive[256];    // per token of the workgroup: has a kept pair (plan_positions_block)
     int R, unit_row0;
 };
 
@@ -548,26 +555,30 @@ __device__ __forceinline__ bool place_pair(const BlockPlan &bp, const Shape &s, 
 __device__ __forceinline__ void plan_positions_block(BlockPlan &bp, int b, const int32_t *__restrict__ topk_idx,
                                                      const PlanPtrs &p, const Shape &s)
 {
-    constexpr int PRE = 8;      // pairs per token fetched before the table reduction, to overlap their latency
+    constexpr int PRE = 8;      // pairs per lane fetched before the table reduction, to overlap their latency
     const int E = s.E, k = s.k, C = s.C;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int u = b / s.bpu, ib = b - u * s.bpu;
     const int t_begin = u * s.Tu + ib * s.TB;
     int nt = s.Tu - ib * s.TB;
     if (nt > s.TB) nt = s.TB;
-    const int t = t_begin + tid;
-    const bool active = tid < nt;
+    // One (token, choice) pair per lane and pass, in the tables' own order: loads and stores of the per-pair
+    // tables are contiguous across the lanes.
+    const int npairs = nt * k, nthr = blockDim.x;
+    const size_t pair0 = (size_t)t_begin * k;
 
     int e_pre[PRE], r_pre[PRE];
 #pragma unroll
-    for (int j = 0; j < PRE; ++j) {
-        e_pre[j] = 0;
-        r_pre[j] = 0;
-        if (active && j < k) {
-            e_pre[j] = topk_idx[(size_t)t * k + j];
-            r_pre[j] = p.local_rank[(size_t)t * k + j];
+    for (int q = 0; q < PRE; ++q) {
+        e_pre[q] = 0;
+        r_pre[q] = 0;
+        const int idx = tid + q * nthr;
+        if (idx < npairs) {
+            e_pre[q] = topk_idx[pair0 + idx];
+            r_pre[q] = p.local_rank[pair0 + idx];
         }
     }
+    for (int i = tid; i < s.TB; i += nthr) bp.alive[i] = 0;      // block_plan's barriers order this before its use
     block_plan(bp, b, p, s);
 
     for (int e = tid; e < E; e += blockDim.x) {
@@ -614,25 +625,29 @@ __device__ __forceinline__ void plan_positions_block(BlockPlan &bp, int b, const
         }
     }
 
-    bool any = false;
-    if (active) {
-        auto place = [&](int j, int e, int lr) {
-            int pf, ps, fo;
-            if (place_pair(bp, s, e, lr, pf, ps, fo)) {
-                p.row_map[ps] = pf;
-                p.final_order[fo] = ps;
-                any = true;
-            }
-            p.pos_final[(size_t)t * k + j] = pf;
-            p.pos_stage[(size_t)t * k + j] = ps;
-        };
+    auto place = [&](int idx, int e, int lr) {
+        int pf, ps, fo;
+        if (place_pair(bp, s, e, lr, pf, ps, fo)) {
+            p.row_map[ps] = pf;
+            p.final_order[fo] = ps;
+            bp.alive[idx / k] = 1;
+        }
+        p.pos_final[pair0 + idx] = pf;
+        p.pos_stage[pair0 + idx] = ps;
+    };
 #pragma unroll
-        for (int j = 0; j < PRE; ++j)
-            if (j < k) place(j, e_pre[j], r_pre[j]);
-        for (int j = PRE; j < k; ++j) place(j, topk_idx[(size_t)t * k + j], p.local_rank[(size_t)t * k + j]);
+    for (int q = 0; q < PRE; ++q) {
+        const int idx = tid + q * nthr;
+        if (idx < npairs) place(idx, e_pre[q], r_pre[q]);
     }
-    const unsigned long long m = __ballot(any);
-    if (lane == 0 && m) atomicAdd(&p.meta[META_ALIVE], __popcll(m));
+    for (int idx = tid + PRE * nthr; idx < npairs; idx += nthr) place(idx, topk_idx[pair0 + idx], p.local_rank[pair0 + idx]);
+    __syncthreads();
+    // tokens with a kept pair
+    for (int i0 = 0; i0 < nt; i0 += nthr) {
+        const int i = i0 + tid;
+        const unsigned long long m = __ballot(i < nt && bp.alive[i] != 0);
+        if (lane == 0 && m) atomicAdd(&p.meta[META_ALIVE], __popcll(m));
+    }
 }
 
 __global__ __launch_bounds__(256) void plan_positions_kernel(const int32_t *__restrict__ topk_idx, PlanPtrs p, Shape s)
