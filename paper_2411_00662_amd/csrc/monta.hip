@@ -1134,13 +1134,18 @@ int launch_unregather_combine(const Geometry &g, const PlanPtrs &p, int dtype, c
     u32x4 *sv = static_cast<u32x4 *>(y_stage), *ov = static_cast<u32x4 *>(out);
     const dim3 grid(n_unreg + n_comb), block(kMoverThreads);
     ProfScope ps(n_unreg && n_comb ? MONTA_K_UNREGATHER_COMBINE : (n_unreg ? MONTA_K_UNREGATHER : MONTA_K_COMBINE), st);
+    const bool pf = s.k >= 3 && s.k <= s.lpr;       // as in monta_combine
+#define MONTA_LAUNCH_UC(BF, NV_, PF_)                                                                                    \
+    hipLaunchKernelGGL((unregather_combine_kernel<BF, NV_, PF_>), grid, block, 0, st, yv, sv, gates, ov, p, s, u0, u1, t0, \
+                       nt, n_unreg)
     if (dtype == MONTA_BF16) {
-        if (wide) hipLaunchKernelGGL((unregather_combine_kernel<true, 4>), grid, block, 0, st, yv, sv, gates, ov, p, s, u0, u1, t0, nt, n_unreg);
-        else hipLaunchKernelGGL((unregather_combine_kernel<true, 2>), grid, block, 0, st, yv, sv, gates, ov, p, s, u0, u1, t0, nt, n_unreg);
+        if (pf) { if (wide) MONTA_LAUNCH_UC(true, 4, true); else MONTA_LAUNCH_UC(true, 2, true); }
+        else { if (wide) MONTA_LAUNCH_UC(true, 4, false); else MONTA_LAUNCH_UC(true, 2, false); }
     } else {
-        if (wide) hipLaunchKernelGGL((unregather_combine_kernel<false, 4>), grid, block, 0, st, yv, sv, gates, ov, p, s, u0, u1, t0, nt, n_unreg);
-        else hipLaunchKernelGGL((unregather_combine_kernel<false, 2>), grid, block, 0, st, yv, sv, gates, ov, p, s, u0, u1, t0, nt, n_unreg);
+        if (pf) { if (wide) MONTA_LAUNCH_UC(false, 4, true); else MONTA_LAUNCH_UC(false, 2, true); }
+        else { if (wide) MONTA_LAUNCH_UC(false, 4, false); else MONTA_LAUNCH_UC(false, 2, false); }
     }
+#undef MONTA_LAUNCH_UC
     HIP_TRY(hipGetLastError());
     return MONTA_OK;
 }

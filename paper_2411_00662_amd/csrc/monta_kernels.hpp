@@ -1188,7 +1188,8 @@ __global__ __launch_bounds__(kMoverThreads) void unregather_kernel(const u32x4 *
 // One grid, up to two jobs in disjoint, interleaved workgroups: the unit-major rows of units [u0, u1)
 // are fetched back from y (skipped if u0 >= u1) while the tokens [t0, t0+nt) of the slice before are
 // combined from rows fetched by the previous launch (skipped if nt == 0).
-template <bool BF16, int NV>
+// PF: the software-pipelined scale-add (three or more choices per token), as in combine_pf_kernel.
+template <bool BF16, int NV, bool PF = false>
 __global__ __launch_bounds__(kMoverThreads) void unregather_combine_kernel(const u32x4 *__restrict__ y,
                                                                            u32x4 *y_stage,
                                                                            const float *__restrict__ gates,
@@ -1212,8 +1213,12 @@ __global__ __launch_bounds__(kMoverThreads) void unregather_combine_kernel(const
         if (u0 < u1) unregather_rows(y, y_stage, p.row_map, s, p.unit_rows[u0], p.unit_rows[u1], idx, n_unreg_wg);
     } else if (nt > 0) {
         with_policy(s.cache & NT_COMB_LD, s.cache & NT_COMB_ST, [&](auto l, auto st) {
-            combine_rows_t<BF16, NV, decltype(l)::value, decltype(st)::value>(y_stage, gates, out, p.pos_stage, s, t0,
-                                                                              nt, idx, n_comb_wg);
+            if (PF)
+                combine_rows_pf_t<BF16, NV, decltype(l)::value, decltype(st)::value>(y_stage, gates, out, p.pos_stage, s,
+                                                                                     t0, nt, idx, n_comb_wg);
+            else
+                combine_rows_t<BF16, NV, decltype(l)::value, decltype(st)::value>(y_stage, gates, out, p.pos_stage, s, t0,
+                                                                                  nt, idx, n_comb_wg);
         });
     }
 }
