@@ -121,7 +121,6 @@ typedef struct monta_ws_layout {
     int64_t off_block_counts;/* [num_blocks][E] internal                                        */
     int64_t off_block_base;  /* [num_blocks][E] internal                                        */
     int64_t off_local_rank;  /* [T][k] internal: rank of a pair inside its route workgroup      */
-    int64_t off_final_order; /* [max_rows] internal: STAGE rows of each slice listed expert by expert */
     int64_t off_kept_prefix; /* [E+1] internal: exclusive scan of kept (= offsets when compact)    */
 } monta_ws_layout;
 

@@ -45,7 +45,7 @@ class monta_ws_layout(ctypes.Structure):
                 ("off_unit_rows", ctypes.c_int64), ("off_pos_final", ctypes.c_int64),
                 ("off_pos_stage", ctypes.c_int64), ("off_row_map", ctypes.c_int64),
                 ("off_block_counts", ctypes.c_int64), ("off_block_base", ctypes.c_int64),
-                ("off_local_rank", ctypes.c_int64), ("off_final_order", ctypes.c_int64),
+                ("off_local_rank", ctypes.c_int64),
                 ("off_kept_prefix", ctypes.c_int64)]
 
 

@@ -84,8 +84,7 @@ _TABLES = [("meta", "off_meta", lambda c, L: (16,)),
            ("unit_rows", "off_unit_rows", lambda c, L: (L.units + 1,)),
            ("pos_final", "off_pos_final", lambda c, L: (c.tokens, c.top_k)),
            ("pos_stage", "off_pos_stage", lambda c, L: (c.tokens, c.top_k)),
-           ("row_map", "off_row_map", lambda c, L: (L.max_rows,)),
-           ("final_order", "off_final_order", lambda c, L: (L.max_rows,))]
+           ("row_map", "off_row_map", lambda c, L: (L.max_rows,))]
 
 
 def read_tables(cfg, ws) -> dict:

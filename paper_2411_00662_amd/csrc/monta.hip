@@ -190,7 +190,6 @@ void fill_layout(const Geometry &g, monta_ws_layout *L)
     L->off_block_counts = take((int64_t)s.num_blocks * s.E);
     L->off_block_base = take((int64_t)s.num_blocks * s.E);
     L->off_local_rank = take((int64_t)s.T * s.k);
-    L->off_final_order = take(g.max_rows);
     L->off_kept_prefix = take(s.E + 1);
     L->ws_bytes = off;
 }
@@ -217,7 +216,6 @@ PlanPtrs plan_ptrs(const Geometry &g, const void *ws)
     p.block_counts = at(L.off_block_counts);
     p.block_base = at(L.off_block_base);
     p.local_rank = at(L.off_local_rank);
-    p.final_order = at(L.off_final_order);
     p.kept_prefix = at(L.off_kept_prefix);
     return p;
 }

@@ -28,7 +28,7 @@ enum { META_R = 0, META_ALIVE = 1, META_C = 2, META_DONE = 3, META_FINAL_ROWS = 
 
 struct PlanPtrs {
     int32_t *meta, *counts, *kept, *offsets, *n, *stage_off, *unit_base, *send_rows, *unit_rows;
-    int32_t *pos_final, *pos_stage, *row_map, *block_counts, *block_base, *local_rank, *final_order, *kept_prefix;
+    int32_t *pos_final, *pos_stage, *row_map, *block_counts, *block_base, *local_rank, *kept_prefix;
 };
 
 struct Shape {
@@ -358,7 +358,6 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t *__restric
                 // always true for tables built by route_plan_kernel; guards a workspace that was never initialised
                 if ((unsigned)pf < (unsigned)s.max_rows && (unsigned)ps < (unsigned)s.max_rows) {
                     p.row_map[ps] = pf;
-                    p.final_order[ps] = ps;     // this path keeps STAGE order for the regather walk
                     any = true;
                 } else {
                     pf = ps = -1;
@@ -381,9 +380,6 @@ struct BlockPlan {
     int off[256];      // offsets[e]: first FINAL row of expert e
     int kpre[256];     // exclusive scan of the kept counts (= off when the layout is compact)
     int stage[256];    // stage_off[u][e]: first STAGE row of block (u, e)
-    int sbefore[256];  // pairs of e in slices before b's slice
-    int sin[256];      // pairs of e in b's slice
-    int forder[256];   // index of block (u, e)'s first row when the slice's rows are listed expert by expert
     int alive[256];    // per token of the workgroup: has a kept pair (plan_positions_block)
     int R, unit_row0;
 };
@@ -391,13 +387,13 @@ struct BlockPlan {
 // One lane's share of the histogram-table reduction of block_plan: the counters of expert e in blocks bl, bl + bstep,
 // ..., LD loads requested before any is added up.
 struct BlockSums {
-    int total, before, unit, pre, sbefore, sin;
+    int total, before, unit, pre;
 };
 template <int LD>
 __device__ __forceinline__ BlockSums sum_blocks(const int32_t *__restrict__ block_counts, int E, int e, int bl, int bstep,
-                                                int nblk, int b, int first, int last, int sfirst, int slast)
+                                                int nblk, int b, int first, int last)
 {
-    BlockSums a = {0, 0, 0, 0, 0, 0};
+    BlockSums a = {0, 0, 0, 0};
     for (int bb0 = bl; bb0 < nblk; bb0 += bstep * LD) {
         int cnt[LD];
 #pragma unroll
@@ -415,8 +411,6 @@ __device__ __forceinline__ BlockSums sum_blocks(const int32_t *__restrict__ bloc
                 a.unit += c;
                 if (bb < b) a.pre += c;
             }
-            if (bb < sfirst) a.sbefore += c;
-            else if (bb < slast) a.sin += c;
         }
     }
     return a;
@@ -434,12 +428,11 @@ __device__ __forceinline__ void block_plan(BlockPlan &bp, int b, const PlanPtrs 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int u = b / s.bpu;
     for (int e = tid; e < E; e += blockDim.x)
-        bp.before[e] = bp.unit[e] = bp.pre[e] = bp.total[e] = bp.sbefore[e] = bp.sin[e] = 0;
+        bp.before[e] = bp.unit[e] = bp.pre[e] = bp.total[e] = 0;
     __syncthreads();
     {
         const int total = s.num_blocks * E;
         const int first = u * s.bpu, last = first + s.bpu;     // blocks of this unit: [first, last)
-        const int sfirst = (u / s.tp) * s.tp * s.bpu, slast = sfirst + s.tp * s.bpu;   // blocks of this slice
         const int nthr = blockDim.x;
         if (nthr % E == 0) {
             // A lane meets one expert only and sums in registers, with one LDS update at the end.  The table
@@ -451,16 +444,12 @@ __device__ __forceinline__ void block_plan(BlockPlan &bp, int b, const PlanPtrs 
             const int bl = tid / E, bstep = nthr / E;            // this lane's first block and its stride
             const int nblk = s.num_blocks;
             const BlockSums a = nblk > 4 * bstep
-                                    ? sum_blocks<16>(p.block_counts, E, e, bl, bstep, nblk, b, first, last, sfirst, slast)
-                                    : sum_blocks<1>(p.block_counts, E, e, bl, bstep, nblk, b, first, last, sfirst, slast);
-            const int a_total = a.total, a_before = a.before, a_unit = a.unit, a_pre = a.pre, a_sbefore = a.sbefore,
-                      a_sin = a.sin;
-            if (a_sbefore) atomicAdd(&bp.sbefore[e], a_sbefore);
-            if (a_sin) atomicAdd(&bp.sin[e], a_sin);
-            if (a_total) atomicAdd(&bp.total[e], a_total);
-            if (a_before) atomicAdd(&bp.before[e], a_before);
-            if (a_unit) atomicAdd(&bp.unit[e], a_unit);
-            if (a_pre) atomicAdd(&bp.pre[e], a_pre);
+                                    ? sum_blocks<16>(p.block_counts, E, e, bl, bstep, nblk, b, first, last)
+                                    : sum_blocks<1>(p.block_counts, E, e, bl, bstep, nblk, b, first, last);
+            if (a.total) atomicAdd(&bp.total[e], a.total);
+            if (a.before) atomicAdd(&bp.before[e], a.before);
+            if (a.unit) atomicAdd(&bp.unit[e], a.unit);
+            if (a.pre) atomicAdd(&bp.pre[e], a.pre);
         } else {
             for (int i = tid; i < total; i += nthr) {
                 const int bb = i / E, e = i - bb * E;
@@ -472,54 +461,38 @@ __device__ __forceinline__ void block_plan(BlockPlan &bp, int b, const PlanPtrs 
                     atomicAdd(&bp.unit[e], c);
                     if (bb < b) atomicAdd(&bp.pre[e], c);
                 }
-                if (bb < sfirst) atomicAdd(&bp.sbefore[e], c);
-                else if (bb < slast) atomicAdd(&bp.sin[e], c);
             }
         }
     }
     __syncthreads();
     if (wave == 0) {
-        int carry_off = 0, carry_stage = 0, carry_fo = 0;
+        int carry_off = 0, carry_stage = 0;
         int base_u = 0;     // sum over experts of min(P[u][e], C): first STAGE row of the unit
-        int base_s = 0;     // the same for the first unit of the slice: first STAGE row of the slice
         for (int e0 = 0; e0 < E; e0 += kWave) {
             const int e = e0 + lane;
-            int v = 0, vs = 0;
-            if (e < E) {
-                v = bp.before[e] < C ? bp.before[e] : C;
-                vs = bp.sbefore[e] < C ? bp.sbefore[e] : C;
-            }
+            const int v = e < E ? (bp.before[e] < C ? bp.before[e] : C) : 0;
             const int incl = wave_inclusive_scan(v, lane);
-            const int incl_s = wave_inclusive_scan(vs, lane);
             base_u += __shfl(incl, kWave - 1, kWave);
-            base_s += __shfl(incl_s, kWave - 1, kWave);
         }
         for (int e0 = 0; e0 < E; e0 += kWave) {
             const int e = e0 + lane;
-            int kp = 0, nu = 0, ns = 0, lo = 0, slo = 0;
+            int kp = 0, nu = 0;
             if (e < E) {
                 const int cnt = bp.total[e];
                 kp = cnt < C ? cnt : C;
-                lo = bp.before[e] < C ? bp.before[e] : C;
+                const int lo = bp.before[e] < C ? bp.before[e] : C;
                 const int nxt = bp.before[e] + bp.unit[e];
                 nu = (nxt < C ? nxt : C) - lo;
-                slo = bp.sbefore[e] < C ? bp.sbefore[e] : C;
-                const int snxt = bp.sbefore[e] + bp.sin[e];
-                ns = (snxt < C ? snxt : C) - slo;       // kept rows of expert e in the whole slice
             }
             const int incl_off = wave_inclusive_scan(kp, lane);
             const int incl_st = wave_inclusive_scan(nu, lane);
-            const int incl_fo = wave_inclusive_scan(ns, lane);
             if (e < E) {
                 bp.kpre[e] = carry_off + incl_off - kp;
                 bp.off[e] = s.padded ? e * C : carry_off + incl_off - kp;
                 bp.stage[e] = base_u + carry_stage + incl_st - nu;
-                // expert-major listing of the slice: rows of earlier experts, then this expert's rows of earlier units
-                bp.forder[e] = base_s + carry_fo + incl_fo - ns + (lo - slo);
             }
             carry_off += __shfl(incl_off, kWave - 1, kWave);
             carry_stage += __shfl(incl_st, kWave - 1, kWave);
-            carry_fo += __shfl(incl_fo, kWave - 1, kWave);
         }
         if (lane == 0) {
             bp.R = carry_off;
@@ -530,21 +503,17 @@ __device__ __forceinline__ void block_plan(BlockPlan &bp, int b, const PlanPtrs 
 }
 
 // STAGE and FINAL rows of one pair from the rebuilt scans; false if the pair is dropped.
-// `fo`: the pair's index when the rows of its slice are listed expert by expert (the order regather walks).
-__device__ __forceinline__ bool place_pair(const BlockPlan &bp, const Shape &s, int e, int local_rank, int &pf, int &ps,
-                                           int &fo)
+__device__ __forceinline__ bool place_pair(const BlockPlan &bp, const Shape &s, int e, int local_rank, int &pf, int &ps)
 {
     const int in_unit = bp.pre[e] + local_rank;     // rank among the unit's pairs of expert e
     const int r = bp.before[e] + in_unit;           // global stable rank
-    pf = ps = fo = -1;
+    pf = ps = -1;
     if (r >= s.C) return false;
     pf = bp.off[e] + r;
     ps = bp.stage[e] + in_unit;
-    fo = bp.forder[e] + in_unit;
     // always true for a consistent histogram table; guards a workspace that was never initialised
-    if ((unsigned)pf < (unsigned)s.max_rows && (unsigned)ps < (unsigned)s.max_rows && (unsigned)fo < (unsigned)s.max_rows)
-        return true;
-    pf = ps = fo = -1;
+    if ((unsigned)pf < (unsigned)s.max_rows && (unsigned)ps < (unsigned)s.max_rows) return true;
+    pf = ps = -1;
     return false;
 }
 
@@ -626,10 +595,9 @@ __device__ __forceinline__ void plan_positions_block(BlockPlan &bp, int b, const
     }
 
     auto place = [&](int idx, int e, int lr) {
-        int pf, ps, fo;
-        if (place_pair(bp, s, e, lr, pf, ps, fo)) {
+        int pf, ps;
+        if (place_pair(bp, s, e, lr, pf, ps)) {
             p.row_map[ps] = pf;
-            p.final_order[fo] = ps;
             bp.alive[idx / k] = 1;
         }
         p.pos_final[pair0 + idx] = pf;
@@ -706,23 +674,21 @@ __device__ __forceinline__ void pack_rows(const u32x4 *__restrict__ x, u32x4 *__
     });
 }
 
-// STAGE rows [r0, r1) go to FINAL rows row_map[.]
+// STAGE rows [r0, r1) go to FINAL rows row_map[.], walked in STAGE order: the reads are one contiguous run, the
+// writes one run per (unit, expert) block.  (Walking a slice's rows expert by expert instead, so that the writes
+// of neighbouring workgroups are neighbours, needs a second lookup per row and measured slower on three of four
+// large workloads, 2 % faster on one.)
 // REVERSE: the other direction (the mirrored return path): row row_map[r] of `fin` goes to row r of `stage`.
 template <bool REVERSE, bool NTL, bool NTS>
 __device__ __forceinline__ void regather_rows_t(u32x4 *stage, u32x4 *fin, const int32_t *__restrict__ row_map,
-                                                const int32_t *__restrict__ order, const Shape &s, int r0, int r1,
-                                                int wg, int nwg)
+                                                const Shape &s, int r0, int r1, int wg, int nwg)
 {
     const int lpr = s.lpr, vpr = s.vpr;
     const int rows_per_wg = kMoverThreads / lpr;
     const int sub = threadIdx.x / lpr, lane = threadIdx.x - sub * lpr;
     if (r0 < 0) r0 = 0;
     if (r1 > s.max_rows) r1 = s.max_rows;
-    for (int i = r0 + wg * rows_per_wg + sub; i < r1; i += nwg * rows_per_wg) {
-        // forward: walk the slice's rows expert by expert, so that neighbouring workgroups write neighbouring
-        // FINAL rows and the scatter is on the read side (measured cheaper than scattered writes)
-        const int r = REVERSE ? i : order[i];
-        if ((unsigned)r >= (unsigned)s.max_rows) continue;
+    for (int r = r0 + wg * rows_per_wg + sub; r < r1; r += nwg * rows_per_wg) {
         const int fr = row_map[r];
         if ((unsigned)fr >= (unsigned)s.max_rows) continue;
         const u32x4 *src = REVERSE ? fin + (size_t)fr * vpr : stage + (size_t)r * vpr;
@@ -767,8 +733,8 @@ __device__ __forceinline__ void regather_rows(const u32x4 *__restrict__ stage, u
                                               const PlanPtrs &p, const Shape &s, int r0, int r1, int wg, int nwg)
 {
     with_policy(s.cache & NT_REG_LD, s.cache & NT_REG_ST, [&](auto l, auto st) {
-        regather_rows_t<false, decltype(l)::value, decltype(st)::value>(const_cast<u32x4 *>(stage), fin, p.row_map,
-                                                                        p.final_order, s, r0, r1, wg, nwg);
+        regather_rows_t<false, decltype(l)::value, decltype(st)::value>(const_cast<u32x4 *>(stage), fin, p.row_map, s, r0,
+                                                                        r1, wg, nwg);
     });
 }
 
@@ -778,8 +744,8 @@ __device__ __forceinline__ void unregather_rows(const u32x4 *__restrict__ y, u32
                                                 int r1, int wg, int nwg)
 {
     with_policy(s.cache & NT_REG_LD, s.cache & NT_REG_ST, [&](auto l, auto st) {
-        regather_rows_t<true, decltype(l)::value, decltype(st)::value>(y_stage, const_cast<u32x4 *>(y), row_map, nullptr,
-                                                                       s, r0, r1, wg, nwg);
+        regather_rows_t<true, decltype(l)::value, decltype(st)::value>(y_stage, const_cast<u32x4 *>(y), row_map, s, r0, r1,
+                                                                       wg, nwg);
     });
 }
 
@@ -815,8 +781,8 @@ __device__ __forceinline__ void pack_rows_selfplan_t(BlockPlan &bp, const u32x4 
                 if (v0 + q * lpr < vpr) val[q] = ld16<NTL>(src + v0 + q * lpr);
         }
         for (int j = 0; j < k; ++j) {
-            int pf, ps, fo;
-            if (!place_pair(bp, s, topk_idx[(size_t)t * k + j], p.local_rank[(size_t)t * k + j], pf, ps, fo)) continue;
+            int pf, ps;
+            if (!place_pair(bp, s, topk_idx[(size_t)t * k + j], p.local_rank[(size_t)t * k + j], pf, ps)) continue;
             u32x4 *dst = stage + (size_t)ps * vpr;
 #pragma unroll
             for (int q = 0; q < kVecInFlight; ++q)

@@ -29,9 +29,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_the_header_layout():
-    # int64 + 7 * int32 + float + 2 * int32 = 48 bytes; layout: 3 * int64 + 4 * int32 + 17 * int64
+    # int64 + 7 * int32 + float + 2 * int32 = 48 bytes; layout: 3 * int64 + 4 * int32 + 16 * int64
     assert ctypes.sizeof(B.monta_cfg) == 48
-    assert ctypes.sizeof(B.monta_ws_layout) == 3 * 8 + 4 * 4 + 17 * 8
+    assert ctypes.sizeof(B.monta_ws_layout) == 3 * 8 + 4 * 4 + 16 * 8
 
 
 def test_workspace_query_named_workloads():

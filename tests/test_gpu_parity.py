@@ -107,18 +107,6 @@ def check_against_oracle(w, logits, x, got, ref=None, canary=0xA5):
     live = pl.pos_stage >= 0
     rm[pl.pos_stage[live]] = pl.pos_final[live]
     np.testing.assert_array_equal(got["row_map"][:pl.R], rm)
-    # the order in which regather walks a slice's rows: a permutation of the slice's STAGE range; either STAGE
-    # order itself (ticketed plan) or the slice's rows listed expert by expert (per-workgroup plan)
-    fo = got["final_order"][:pl.R]
-    row_expert = np.empty(pl.R, np.int64)
-    row_expert[pl.pos_stage[live]] = ref.topk_idx[live]
-    expect_em = np.empty(pl.R, np.int64)
-    for j in range(w.slices):
-        a, b_ = int(got["unit_rows"][j * w.tp]), int(got["unit_rows"][(j + 1) * w.tp])
-        rows = np.arange(a, b_)
-        expect_em[a:b_] = rows[np.lexsort((rows, row_expert[a:b_]))]
-        assert np.array_equal(np.sort(fo[a:b_]), rows), "final_order is not a permutation of the slice's rows"
-    assert np.array_equal(fo, expect_em) or np.array_equal(fo, np.arange(pl.R))
     # buffers: bit-exact below R, untouched above
     for name, refbuf, rows in (("stage_full", ref.stage, pl.R), ("final_full", ref.final, pl.final_rows)):
         buf = got[name]
