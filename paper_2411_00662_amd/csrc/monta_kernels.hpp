@@ -644,15 +644,23 @@ __device__ __forceinline__ void pack_rows_t(const u32x4 *__restrict__ x, u32x4 *
     for (int i = wg * rows_per_wg + sub; i < nt; i += nwg * rows_per_wg) {
         const int t = t0 + i;
         const int32_t *pos = pos_stage + (size_t)t * k;
+        const u32x4 *src = x + (size_t)t * vpr;
+        // The first pass of the row is requested before the positions are looked at: the two latencies overlap
+        // instead of adding up.  The price is the row of a token whose choices were all dropped, read in vain
+        // (a few percent of the tokens of a workload with heavy drops, none otherwise).
+        u32x4 val[kVecInFlight];
+#pragma unroll
+        for (int q = 0; q < kVecInFlight; ++q)
+            if (lane + q * lpr < vpr) val[q] = ld16<NTL>(src + lane + q * lpr);
         bool any = false;
         for (int j = 0; j < k; ++j) any |= (unsigned)pos[j] < (unsigned)s.max_rows;
-        if (!any) continue;                 // every choice of this token was dropped: its row is never read
-        const u32x4 *src = x + (size_t)t * vpr;
+        if (!any) continue;                 // every choice of this token was dropped
         for (int v0 = lane; v0 < vpr; v0 += lpr * kVecInFlight) {
-            u32x4 val[kVecInFlight];
+            if (v0 != lane) {
 #pragma unroll
-            for (int q = 0; q < kVecInFlight; ++q)
-                if (v0 + q * lpr < vpr) val[q] = ld16<NTL>(src + v0 + q * lpr);
+                for (int q = 0; q < kVecInFlight; ++q)
+                    if (v0 + q * lpr < vpr) val[q] = ld16<NTL>(src + v0 + q * lpr);
+            }
             for (int j = 0; j < k; ++j) {
                 const int ps = pos[j];
                 if ((unsigned)ps >= (unsigned)s.max_rows) continue;   // dropped (-1) or not a row
@@ -689,15 +697,25 @@ __device__ __forceinline__ void regather_rows_t(u32x4 *stage, u32x4 *fin, const 
     if (r0 < 0) r0 = 0;
     if (r1 > s.max_rows) r1 = s.max_rows;
     for (int r = r0 + wg * rows_per_wg + sub; r < r1; r += nwg * rows_per_wg) {
+        u32x4 val[kVecInFlight];
+        if (!REVERSE) {
+            // forward: the source row does not depend on the table, so its first pass is requested before the
+            // destination is looked up
+            const u32x4 *src0 = stage + (size_t)r * vpr;
+#pragma unroll
+            for (int q = 0; q < kVecInFlight; ++q)
+                if (lane + q * lpr < vpr) val[q] = ld16<NTL>(src0 + lane + q * lpr);
+        }
         const int fr = row_map[r];
         if ((unsigned)fr >= (unsigned)s.max_rows) continue;
         const u32x4 *src = REVERSE ? fin + (size_t)fr * vpr : stage + (size_t)r * vpr;
         u32x4 *dst = REVERSE ? stage + (size_t)r * vpr : fin + (size_t)fr * vpr;
         for (int v0 = lane; v0 < vpr; v0 += lpr * kVecInFlight) {
-            u32x4 val[kVecInFlight];
+            if (REVERSE || v0 != lane) {
 #pragma unroll
-            for (int q = 0; q < kVecInFlight; ++q)
-                if (v0 + q * lpr < vpr) val[q] = ld16<NTL>(src + v0 + q * lpr);
+                for (int q = 0; q < kVecInFlight; ++q)
+                    if (v0 + q * lpr < vpr) val[q] = ld16<NTL>(src + v0 + q * lpr);
+            }
 #pragma unroll
             for (int q = 0; q < kVecInFlight; ++q)
                 if (v0 + q * lpr < vpr) st16<NTS>(dst + v0 + q * lpr, val[q]);
