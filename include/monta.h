@@ -251,7 +251,7 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
  * to those calls.  Calls no hipMalloc / hipFree and creates no stream or event: pipeline mode 0 is replaced by
  * the size-chosen mode, and with event profiling enabled the call is refused (MONTA_ERR_INVALID).  Problems
  * whose tables (monta_ws_layout.ws_bytes) exceed 16 MiB are refused with MONTA_ERR_TOO_LARGE before any GPU
- * work; the five named workloads need at most 10.2 MiB.  Every call on one GPU shares that GPU's array: the
+ * work; the five named workloads need at most 8.2 MiB.  Every call on one GPU shares that GPU's array: the
  * counters in it are cleared by a small kernel at the start of each call, the tables are overwritten, and two
  * calls that overlap in time on one GPU (different streams or threads) race -- the caller must order them. */
 int monta_route_dispatch_combine_static(const monta_cfg *cfg, const float *logits, const void *x, int32_t *topk_idx,
