@@ -212,11 +212,21 @@ def measure(args, w, steps, warmup, full):
             if S > 1:
                 per_launch["pack_regather"] = sum(ab["pack_s"][j] + ab["regather_s"][j - 1] for j in range(1, S)) / (S - 1)
         if mirror:
-            per_launch["unregather"] = ab["unregather_s"][0]
-            per_launch["combine"] = ab["combine_s"][S - 1]
-            if S > 1:
-                per_launch["unregather_combine"] = sum(ab["unregather_s"][j] + ab["combine_s"][j - 1]
-                                                       for j in range(1, S)) / (S - 1)
+            # the return pipeline: fetch and combine per launch group, as two kernels or co-scheduled; the group
+            # count follows from the launches seen (groups are even)
+            n_uc = round(kernels["unregather_combine"]["launches_per_step"]) if "unregather_combine" in kernels else 0
+            Gm = n_uc + 1 if n_uc else max(1, round(kernels["unregather"]["launches_per_step"]))
+            spg_m = -(-S // Gm)
+            mgroups = [range(lo, min(lo + spg_m, S)) for lo in range(0, S, spg_m)]
+            un_g = [sum(ab["unregather_s"][j] for j in gr) for gr in mgroups]
+            cb_g = [sum(ab["combine_s"][j] for j in gr) for gr in mgroups]
+            if n_uc:
+                per_launch["unregather"] = un_g[0]
+                per_launch["combine"] = cb_g[-1]
+                per_launch["unregather_combine"] = sum(un_g[i] + cb_g[i - 1] for i in range(1, len(mgroups))) / n_uc
+            else:
+                per_launch["unregather"] = sum(un_g) / len(un_g)
+                per_launch["combine"] = sum(cb_g) / len(cb_g)
         movers = [kname for kname in ("pack", "regather", "pack_regather", "combine", "plan_pack", "unregather",
                                       "unregather_combine", "gate") if kname in kernels]
         dom = max(movers, key=lambda kname: kernels[kname]["us_per_step"])

@@ -271,8 +271,10 @@ int monta_unregather(const monta_cfg *cfg, const void *y, void *y_stage, const v
 int monta_combine_staged(const monta_cfg *cfg, const void *y_stage, const float *gates, void *out, const void *ws,
                          int slice, void *stream);
 
-/* The return pipeline on one stream: launch j fetches slice j back and, in disjoint workgroups of the
- * same grid, combines the tokens of slice j-1 (S+1 launches). */
+/* The return pipeline on one stream.  With pipeline mode 0 or 1, launch j fetches slice j back and, in disjoint
+ * workgroups of the same grid, combines the tokens of slice j-1 (S+1 launches); with mode 2, fetch and combine of
+ * every slice are two plain kernels; the default (-1) groups consecutive slices as the forward pipeline does
+ * (groups of up to 256 MiB, two plain kernels per group once a group is that large or the problem is one group). */
 int monta_unregather_combine(const monta_cfg *cfg, const void *y, void *y_stage, const float *gates, void *out,
                              const void *ws, void *stream);
 

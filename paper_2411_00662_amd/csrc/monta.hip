@@ -1191,10 +1191,41 @@ int monta_unregather_combine(const monta_cfg *cfg, const void *y, void *y_stage,
     const PlanPtrs p = plan_ptrs(g, ws);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int per_slice = s.tp * s.Tu;
-    // launch j fetches slice j back and combines the tokens of slice j-1
-    for (int j = 0; j <= s.S; ++j) {
-        const int u0 = j < s.S ? j * s.tp : 0, u1 = j < s.S ? (j + 1) * s.tp : 0;
-        const int t0 = j > 0 ? (j - 1) * per_slice : 0, nt = j > 0 ? per_slice : 0;
+    // Launch grouping as in the forward pipeline, by the same measurements: with an explicit pipeline mode launch j
+    // fetches slice j back and, in disjoint workgroups of the same grid, combines the tokens of slice j-1; by
+    // default consecutive slices are grouped until a group's rows reach 256 MiB, and a group that large (or a
+    // problem that is one group) runs as two plain kernels, fetch then combine.
+    int spg = 1;
+    bool serial = false;
+    if (g.modes.pipeline < 0) {
+        const int64_t slice_bytes = slice_rows_bound(g, 1) * g.row_bytes;
+        if (slice_bytes >= kGroupBytes) serial = true;
+        else {
+            spg = (int)(kGroupBytes / slice_bytes);
+            if (spg > s.S) spg = s.S;
+            const int groups = (s.S + spg - 1) / spg;
+            spg = (s.S + groups - 1) / groups;
+            serial = groups == 1 || spg * slice_bytes >= kGroupBytes * 3 / 4;
+        }
+    } else {
+        serial = g.modes.pipeline == 2;
+    }
+    const int G = (s.S + spg - 1) / spg;
+    auto lo = [&](int gi) { return gi * spg; };
+    auto hi = [&](int gi) { return (gi + 1) * spg < s.S ? (gi + 1) * spg : s.S; };
+    if (serial) {
+        for (int gi = 0; gi < G; ++gi) {
+            if ((rc = launch_unregather_combine(g, p, cfg->dtype, y, y_stage, gates, out, lo(gi) * s.tp, hi(gi) * s.tp, 0, 0, st)))
+                return rc;
+            if ((rc = launch_unregather_combine(g, p, cfg->dtype, y, y_stage, gates, out, 0, 0, lo(gi) * per_slice,
+                                                (hi(gi) - lo(gi)) * per_slice, st)))
+                return rc;
+        }
+        return MONTA_OK;
+    }
+    for (int gi = 0; gi <= G; ++gi) {
+        const int u0 = gi < G ? lo(gi) * s.tp : 0, u1 = gi < G ? hi(gi) * s.tp : 0;
+        const int t0 = gi > 0 ? lo(gi - 1) * per_slice : 0, nt = gi > 0 ? (hi(gi - 1) - lo(gi - 1)) * per_slice : 0;
         if ((rc = launch_unregather_combine(g, p, cfg->dtype, y, y_stage, gates, out, u0, u1, t0, nt, st))) return rc;
     }
     return MONTA_OK;
