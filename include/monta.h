@@ -253,7 +253,9 @@ int monta_combine(const monta_cfg *cfg, const void *y, const float *gates, void 
  * whose tables (monta_ws_layout.ws_bytes) exceed 16 MiB are refused with MONTA_ERR_TOO_LARGE before any GPU
  * work; the five named workloads need at most 8.2 MiB.  Every call on one GPU shares that GPU's array: the
  * counters in it are cleared by a small kernel at the start of each call, the tables are overwritten, and two
- * calls that overlap in time on one GPU (different streams or threads) race -- the caller must order them. */
+ * calls that overlap in time on one GPU (different streams or threads) race -- the caller must order them.  The
+ * first call on a device looks the array's address up (hipGetSymbolAddress): make one call before capturing the
+ * entry point into a HIP graph; captured, it records kernel nodes only. */
 int monta_route_dispatch_combine_static(const monta_cfg *cfg, const float *logits, const void *x, int32_t *topk_idx,
                                         float *gates, void *stage, void *final_, void *out, void *stream);
 

@@ -83,3 +83,56 @@ def test_static_scratch_call_on_a_named_workload_and_with_profiling_on(m):
         m.monta_profile_enable(False)
         m.monta_profile_reset()
     torch.cuda.synchronize()
+
+
+def test_static_scratch_call_replayed_from_a_hip_graph(m):
+    """The callers it is for: captured once (after one eager call, which looks the array's address up), replayed
+    on changing inputs with eager work in between; every replay must give the eager bits."""
+    import torch
+    w = Workload("noalloc-graph", 4096, 1024, BF16, 8, 2, 4, 2, 4, 0.8, zipf_s=0.6)
+    cfg = m.make_cfg(w.tokens, w.hidden, w.dtype, w.experts, w.top_k, w.ep, w.tp, w.slices, w.capacity_factor, w.renorm)
+    inputs = [workloads.make_inputs(w, seed=s) for s in (1, 2, 3)]
+    b = m.alloc_buffers(cfg, *inputs[0], canary=0)
+    stream = torch.cuda.Stream()
+
+    def step():
+        m.monta_route_dispatch_combine_static(cfg, b.logits, b.x, b.topk_idx, b.gates, b.stage, b.final, b.out, stream)
+
+    def load(i):
+        logits, x = inputs[i]
+        b.logits.copy_(torch.from_numpy(logits).cuda())
+        b.x.copy_(torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16))
+        torch.cuda.synchronize()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (b.topk_idx, b.gates.view(torch.int32), b.out.view(torch.int16))]
+
+    eager = []
+    for i in range(3):
+        load(i)
+        with torch.cuda.stream(stream):
+            step()
+        eager.append(snapshot())
+    load(0)
+    with torch.cuda.stream(stream):
+        step()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+    for rep in range(2):
+        for i in (2, 0, 1):
+            _say(f"static scratch: graph replay rep={rep} input={i}")
+            load(i)
+            b.out.zero_()
+            b.topk_idx.zero_()
+            graph.replay()
+            got = snapshot()
+            for a_, e_ in zip(got, eager[i]):
+                assert torch.equal(a_, e_)
+            # eager work of the same library between replays (it uses its own workspace, not the static array)
+            b2 = m.alloc_buffers(cfg, *inputs[(i + 1) % 3])
+            m.monta_route_dispatch_regather(cfg, b2.logits, b2.x, b2.topk_idx, b2.gates, b2.stage, b2.final, b2.ws)
+            torch.cuda.synchronize()
+            del b2
